@@ -1,0 +1,165 @@
+/*
+ * rocket.h -- C ABI of the MI355X (gfx950) ROCKET transform library.
+ *
+ * The library computes the hot path of "Making the 'exceptionally fast' ROCKET
+ * model faster": K random dilated, padded, biased 1-D convolution kernels are
+ * applied to every (multivariate) series and each kernel output is pooled
+ * (paper section 3, parts (1) and (2)).
+ *
+ * Notation.  Kernel k has length len in {7,9,11}, dilation d >= 1, padding
+ * p in {0, (len-1)d/2}, a bias, a list of n_ch distinct channels and one weight
+ * row of len floats per listed channel.  For a series x (C rows of L floats)
+ *
+ *     y[t] = bias + sum_c sum_j w[c][j] * x[channel[c]][t + j*d - p],   x = 0 outside [0,L)
+ *     t = 0 .. n-1,   n = L + 2p - (len-1)d      (cross-correlation, no flip)
+ *
+ * Features (section 3.2):
+ *     ROCKET_F_MAX      max_t y[t]
+ *     ROCKET_F_PPV      (1/n) #{t : y[t] > 0}                       Eq. 1-2
+ *     ROCKET_F_SOFTPPV  (1/n) sum_t 1/(1+exp(-(lambda*y[t]+shift)))  Eq. 3-4
+ * The prose under Eq. 3 fixes shift = -3; the printed formula is shift = +3.
+ *
+ * Conventions.  Every function returns ROCKET_OK (0) or a negative error code
+ * and never throws or aborts; rocket_last_error() gives the message of the
+ * last failure on the calling thread.  "host" / "device" below says where a
+ * pointer must live.  All arrays are contiguous.  Device work is enqueued on
+ * the given HIP stream (a hipStream_t passed as void*, NULL = default stream)
+ * and is not synchronised: the caller synchronises the stream before reading
+ * results.  Outputs are overwritten, never accumulated into.  Inputs must be
+ * finite.  A handle may be used from one thread at a time.
+ */
+#ifndef ROCKET_MI355X_H
+#define ROCKET_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    ROCKET_OK = 0,
+    ROCKET_EINVAL = -1,      /* bad argument value (null pointer, size < 1, bad mask, non-finite scalar) */
+    ROCKET_ENOMEM = -2,      /* host or device allocation failed */
+    ROCKET_EHIP = -3,        /* a HIP runtime call or kernel launch failed */
+    ROCKET_ESHAPE = -4,      /* kernel parameters inconsistent with (C, L) */
+    ROCKET_EWORKSPACE = -5   /* workspace missing or smaller than rocket_workspace_bytes() */
+};
+
+/* feature mask bits; output planes appear in bit order */
+enum { ROCKET_F_MAX = 1, ROCKET_F_PPV = 2, ROCKET_F_SOFTPPV = 4 };
+
+/* opaque, library-owned set of K kernels for series of shape C x L */
+typedef struct rocket_kernels rocket_kernels;
+
+/* Borrowed host pointers into a handle; valid until the handle is freed.
+ * weights of kernel k start at weights[w_off[k]] and are channel-major
+ * (n_ch[k] rows of length[k]); its channel list starts at channels[ch_off[k]]. */
+typedef struct rocket_kernels_view {
+    int32_t K, C, L;
+    int64_t total_channels;   /* sum of n_ch          */
+    int64_t total_weights;    /* sum of n_ch * length */
+    const int32_t *length, *dilation, *padding, *n_ch;   /* [K] */
+    const float *bias;                                   /* [K] */
+    const int64_t *ch_off, *w_off;                       /* [K+1] */
+    const int32_t *channels;                             /* [total_channels] */
+    const float *weights;                                /* [total_weights] */
+} rocket_kernels_view;
+
+/*
+ * Random kernel initialisation (section 3.1): length uniform on {7,9,11};
+ * N(0,1) weights, mean-centred per (kernel, channel) row; bias uniform on
+ * [-1,1); dilation floor(2^(u*log2((L-1)/(len-1)))); a fair coin between
+ * "same" padding and none; a random subset of floor(2^(u*log2(min(C,9)+1)))
+ * channels.  Kernel k is drawn from its own SplitMix64 stream of (seed, k), so
+ * the result is a pure function of (seed, K, C, L).  Host only: no GPU needed.
+ * Requires K, C >= 1 and L >= 11.  *out receives a new handle (free it with
+ * rocket_free_kernels).
+ */
+int rocket_make_kernels(uint64_t seed, int32_t K, int32_t C, int32_t L, rocket_kernels **out);
+
+/*
+ * Builds a handle from kernels generated elsewhere (the paper loads externally
+ * generated kernels into its model, section 3.1).  All pointers are host
+ * arrays that are copied: length, dilation, padding, n_ch, bias have K entries;
+ * channels has sum(n_ch) entries; weights has sum(n_ch*length) entries, kernel
+ * after kernel, channel-major.  Checks: length in {7,9,11}; d >= 1;
+ * padding is 0 or (len-1)d/2; n = L + 2p - (len-1)d >= 1; 1 <= n_ch <= C;
+ * channels distinct and in [0,C); weights and biases finite.  Violations give
+ * ROCKET_ESHAPE.
+ */
+int rocket_kernels_import(int32_t K, int32_t C, int32_t L,
+                          const int32_t *length, const int32_t *dilation, const int32_t *padding,
+                          const float *bias, const int32_t *n_ch, const int32_t *channels,
+                          const float *weights, rocket_kernels **out);
+
+/* Fills *view with borrowed host pointers to the handle's arrays. */
+int rocket_kernels_view_get(const rocket_kernels *kernels, rocket_kernels_view *view);
+
+/* Replaces all weights and/or all biases (host arrays in the handle's layout;
+ * either may be NULL = keep).  For training loops and finite differences. */
+int rocket_kernels_set_params(rocket_kernels *kernels, const float *weights, const float *bias);
+
+/* Number of output planes of a feature mask (its population count), 0 if invalid. */
+int32_t rocket_num_features(uint32_t feature_mask);
+
+/*
+ * Bytes of device workspace that rocket_transform (backward = 0) or
+ * rocket_soft_ppv_backward (backward = 1) needs for a batch of B series.
+ * Returns 0 on invalid arguments.  The workspace holds a zero-padded copy of
+ * the batch (so that dilated reads never leave a row) and, for the backward
+ * pass, per-series partial gradients.  Its contents are scratch.
+ */
+size_t rocket_workspace_bytes(const rocket_kernels *kernels, int32_t B, uint32_t feature_mask, int backward);
+
+/*
+ * The transform, parts (1) and (2) of section 3 fused: x_dev is device memory,
+ * B x C x L float32 (row-major, L contiguous) with C, L those of the handle;
+ * out_dev is device memory, B x (F*K) float32 with F = rocket_num_features(mask):
+ * out[b*F*K + f*K + k] is feature plane f (bit order of the mask) of kernel k
+ * in the handle's kernel order.  workspace_dev: device memory of at least
+ * rocket_workspace_bytes(kernels, B, mask, 0) bytes, 256-byte aligned.
+ * lambda and shift are used by ROCKET_F_SOFTPPV only (the paper's reading is
+ * shift = -3).  On first use the handle uploads its parameters to the current
+ * device (one hipMalloc); later calls allocate nothing.
+ */
+int rocket_transform(rocket_kernels *kernels, const float *x_dev, int32_t B, uint32_t feature_mask,
+                     float lambda, float shift, float *out_dev,
+                     void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward pass through the pooling (the gradient flow that softPPV allows,
+ * section 3.2): given grad_out_dev (device, same layout as the transform's
+ * output for feature_mask, which must contain ROCKET_F_SOFTPPV), computes the
+ * gradient of sum(grad_out * features) with respect to the stored weights and
+ * biases, summed over the batch:
+ *     s_t = 1/(1+exp(-(lambda*y_t+shift))),  q_t = g_soft[b,k]*(lambda/n)*s_t*(1-s_t)
+ *     grad_b[k]       = sum_b sum_t q_t
+ *     grad_w[k][c][j] = sum_b sum_t q_t * x_b[channel[c]][t + j*d - p]
+ * If include_max != 0 (mask must contain ROCKET_F_MAX) the max plane adds its
+ * sub-gradient at the first position attaining the maximum.  The PPV plane has
+ * zero gradient and is ignored.  grad_w_dev: device, total_weights floats in
+ * the layout of `weights`; grad_b_dev: device, K floats.  No gradient with
+ * respect to x.  workspace: rocket_workspace_bytes(kernels, B, mask, 1) bytes.
+ */
+int rocket_soft_ppv_backward(rocket_kernels *kernels, const float *x_dev, int32_t B, uint32_t feature_mask,
+                             const float *grad_out_dev, float lambda, float shift, int include_max,
+                             float *grad_w_dev, float *grad_b_dev,
+                             void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/* Algorithmic work of one call, for roofline accounting: *conv_fma receives
+ * sum_k n_k*n_ch_k*len_k (fused multiply-adds per series of the forward conv),
+ * *outputs receives sum_k n_k (pooled positions per series). */
+int rocket_work_per_series(const rocket_kernels *kernels, double *conv_fma, double *outputs);
+
+/* Frees a handle and its device mirror; NULL is allowed. */
+void rocket_free_kernels(rocket_kernels *kernels);
+
+/* Message of the last error on this thread ("" if none); static storage. */
+const char *rocket_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROCKET_MI355X_H */

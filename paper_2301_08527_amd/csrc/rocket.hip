@@ -1,0 +1,547 @@
+// ROCKET transform for MI355X (gfx950): C-ABI entry points, launch logic and
+// the HIP kernels.  See include/rocket.h for the contract of every entry point.
+//
+// Work decomposition of the forward pass (paper section 3, parts (1)-(2)):
+//   one workgroup (256 lanes) owns one (series b, kernel k) pair and produces
+//   its pooled features, so no cross-workgroup combine is needed.
+//   The n outputs of a kernel with dilation d are viewed as a grid of rows of d
+//   consecutive positions: t = m*d + r.  A lane owns a vertical strip of R rows
+//   in one column r, i.e. outputs t0, t0+d, ..., t0+(R-1)d.  Those R outputs
+//   read the R+len-1 inputs x[t0-p+i*d]; each input is loaded once and feeds up
+//   to len fused multiply-adds from registers.  Neighbouring lanes own
+//   neighbouring columns, so every load instruction of a wavefront reads
+//   consecutive floats.  The row range is cut into bands of 16, 8, 4, 2 and 1
+//   rows (binary decomposition of the row count) plus the partial last row, so
+//   every strip is fully valid and the pooling needs no masks.
+//   Weights are wavefront-uniform (scalar registers); max / PPV count / softPPV
+//   sum stay in registers and are closed with wavefront shuffles.
+//   The batch is first copied into a zero-padded workspace so that no dilated
+//   read leaves its row and "same" padding needs no bounds checks.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "rocket_internal.hpp"
+
+// ------------------------------------------------------------------ errors
+
+static thread_local std::string g_last_error;
+
+void rk_set_error(const std::string &msg) { g_last_error = msg; }
+
+int rk_fail(int code, const std::string &msg)
+{
+    g_last_error = msg;
+    return code;
+}
+
+#define RK_HIP(call)                                                                   \
+    do {                                                                               \
+        hipError_t e_ = (call);                                                        \
+        if (e_ != hipSuccess)                                                          \
+            return rk_fail(ROCKET_EHIP, std::string(#call) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+// ------------------------------------------------------------------ host plan
+
+static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+int rk_finish_handle(rocket_kernels &h)
+{
+    const int32_t K = h.K;
+    h.ch_off.assign(K + 1, 0);
+    h.w_off.assign(K + 1, 0);
+    h.pad_max = 0;
+    h.conv_fma = 0.0;
+    h.outputs = 0.0;
+    std::vector<double> cost(K);
+    for (int32_t k = 0; k < K; ++k) {
+        h.ch_off[k + 1] = h.ch_off[k] + h.n_ch[k];
+        h.w_off[k + 1] = h.w_off[k] + static_cast<int64_t>(h.n_ch[k]) * h.length[k];
+        const int64_t n = static_cast<int64_t>(h.L) + 2LL * h.padding[k] -
+                          static_cast<int64_t>(h.length[k] - 1) * h.dilation[k];
+        if (n < 1) return rk_fail(ROCKET_ESHAPE, "kernel " + std::to_string(k) + " has no output position");
+        h.pad_max = std::max(h.pad_max, h.padding[k]);
+        cost[k] = static_cast<double>(n) * h.n_ch[k] * h.length[k];
+        h.conv_fma += cost[k];
+        h.outputs += static_cast<double>(n);
+    }
+    if (h.w_off[K] > INT32_MAX || h.ch_off[K] > INT32_MAX)
+        return rk_fail(ROCKET_EINVAL, "too many weights for 32-bit offsets");
+    // launch order: most expensive kernels first, so the last workgroups to
+    // start are the cheapest and the tail of the launch is short
+    h.order.resize(K);
+    for (int32_t k = 0; k < K; ++k) h.order[k] = k;
+    std::stable_sort(h.order.begin(), h.order.end(),
+                     [&](int32_t a, int32_t b) { return cost[a] > cost[b]; });
+    // padded rows: `lead` zeros, the L samples, then at least pad_max zeros
+    h.lead = static_cast<int32_t>(round_up(h.pad_max, 64));
+    h.row_len = round_up(static_cast<int64_t>(h.lead) + h.L + h.pad_max, 64);
+    h.params_dirty = true;
+    return ROCKET_OK;
+}
+
+// ------------------------------------------------------------------ handles
+
+extern "C" const char *rocket_last_error(void) { return g_last_error.c_str(); }
+
+extern "C" int32_t rocket_num_features(uint32_t mask)
+{
+    if (mask == 0 || (mask & ~7u)) return 0;
+    return static_cast<int32_t>(__builtin_popcount(mask));
+}
+
+extern "C" int rocket_make_kernels(uint64_t seed, int32_t K, int32_t C, int32_t L, rocket_kernels **out)
+{
+    if (!out) return rk_fail(ROCKET_EINVAL, "rocket_make_kernels: out is NULL");
+    *out = nullptr;
+    if (K < 1 || C < 1) return rk_fail(ROCKET_EINVAL, "rocket_make_kernels: K and C must be >= 1");
+    if (L < 11) return rk_fail(ROCKET_EINVAL, "rocket_make_kernels: L must be >= 11");
+    rocket_kernels *h = new (std::nothrow) rocket_kernels;
+    if (!h) return rk_fail(ROCKET_ENOMEM, "rocket_make_kernels: out of host memory");
+    try {
+        h->K = K; h->C = C; h->L = L;
+        rk_sample_kernels(seed, *h);
+        int rc = rk_finish_handle(*h);
+        if (rc != ROCKET_OK) { delete h; return rc; }
+    } catch (const std::bad_alloc &) {
+        delete h;
+        return rk_fail(ROCKET_ENOMEM, "rocket_make_kernels: out of host memory");
+    }
+    *out = h;
+    return ROCKET_OK;
+}
+
+extern "C" int rocket_kernels_import(int32_t K, int32_t C, int32_t L,
+                                     const int32_t *length, const int32_t *dilation, const int32_t *padding,
+                                     const float *bias, const int32_t *n_ch, const int32_t *channels,
+                                     const float *weights, rocket_kernels **out)
+{
+    if (!out) return rk_fail(ROCKET_EINVAL, "rocket_kernels_import: out is NULL");
+    *out = nullptr;
+    if (!length || !dilation || !padding || !bias || !n_ch || !channels || !weights)
+        return rk_fail(ROCKET_EINVAL, "rocket_kernels_import: NULL array");
+    if (K < 1 || C < 1 || L < 1) return rk_fail(ROCKET_EINVAL, "rocket_kernels_import: K, C, L must be >= 1");
+    rocket_kernels *h = new (std::nothrow) rocket_kernels;
+    if (!h) return rk_fail(ROCKET_ENOMEM, "rocket_kernels_import: out of host memory");
+    try {
+        h->K = K; h->C = C; h->L = L;
+        int64_t nc = 0, nw = 0;
+        std::vector<char> seen(C);
+        for (int32_t k = 0; k < K; ++k) {
+            const std::string who = "rocket_kernels_import: kernel " + std::to_string(k);
+            const int32_t len = length[k], d = dilation[k], p = padding[k], m = n_ch[k];
+            if (len != 7 && len != 9 && len != 11) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": length not in {7,9,11}"); }
+            if (d < 1) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": dilation < 1"); }
+            const int64_t span = static_cast<int64_t>(len - 1) * d;
+            if (p != 0 && p != span / 2) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": padding is neither 0 nor (len-1)d/2"); }
+            if (static_cast<int64_t>(L) + 2LL * p - span < 1) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": no output position"); }
+            if (m < 1 || m > C) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": n_ch outside [1,C]"); }
+            std::fill(seen.begin(), seen.end(), 0);
+            for (int32_t c = 0; c < m; ++c) {
+                const int32_t ch = channels[nc + c];
+                if (ch < 0 || ch >= C || seen[ch]) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": channel out of range or repeated"); }
+                seen[ch] = 1;
+            }
+            if (!std::isfinite(bias[k])) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": bias not finite"); }
+            for (int64_t i = 0; i < static_cast<int64_t>(m) * len; ++i)
+                if (!std::isfinite(weights[nw + i])) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": weight not finite"); }
+            nc += m;
+            nw += static_cast<int64_t>(m) * len;
+        }
+        h->length.assign(length, length + K);
+        h->dilation.assign(dilation, dilation + K);
+        h->padding.assign(padding, padding + K);
+        h->n_ch.assign(n_ch, n_ch + K);
+        h->bias.assign(bias, bias + K);
+        h->channels.assign(channels, channels + nc);
+        h->weights.assign(weights, weights + nw);
+        int rc = rk_finish_handle(*h);
+        if (rc != ROCKET_OK) { delete h; return rc; }
+    } catch (const std::bad_alloc &) {
+        delete h;
+        return rk_fail(ROCKET_ENOMEM, "rocket_kernels_import: out of host memory");
+    }
+    *out = h;
+    return ROCKET_OK;
+}
+
+extern "C" int rocket_kernels_view_get(const rocket_kernels *h, rocket_kernels_view *v)
+{
+    if (!h || !v) return rk_fail(ROCKET_EINVAL, "rocket_kernels_view_get: NULL argument");
+    v->K = h->K; v->C = h->C; v->L = h->L;
+    v->total_channels = h->ch_off[h->K];
+    v->total_weights = h->w_off[h->K];
+    v->length = h->length.data(); v->dilation = h->dilation.data(); v->padding = h->padding.data();
+    v->n_ch = h->n_ch.data(); v->bias = h->bias.data();
+    v->ch_off = h->ch_off.data(); v->w_off = h->w_off.data();
+    v->channels = h->channels.data(); v->weights = h->weights.data();
+    return ROCKET_OK;
+}
+
+extern "C" int rocket_kernels_set_params(rocket_kernels *h, const float *weights, const float *bias)
+{
+    if (!h) return rk_fail(ROCKET_EINVAL, "rocket_kernels_set_params: NULL handle");
+    if (weights) {
+        for (size_t i = 0; i < h->weights.size(); ++i)
+            if (!std::isfinite(weights[i])) return rk_fail(ROCKET_EINVAL, "rocket_kernels_set_params: weight not finite");
+        std::copy(weights, weights + h->weights.size(), h->weights.begin());
+    }
+    if (bias) {
+        for (int32_t k = 0; k < h->K; ++k)
+            if (!std::isfinite(bias[k])) return rk_fail(ROCKET_EINVAL, "rocket_kernels_set_params: bias not finite");
+        std::copy(bias, bias + h->K, h->bias.begin());
+    }
+    h->params_dirty = true;
+    return ROCKET_OK;
+}
+
+extern "C" int rocket_work_per_series(const rocket_kernels *h, double *conv_fma, double *outputs)
+{
+    if (!h) return rk_fail(ROCKET_EINVAL, "rocket_work_per_series: NULL handle");
+    if (conv_fma) *conv_fma = h->conv_fma;
+    if (outputs) *outputs = h->outputs;
+    return ROCKET_OK;
+}
+
+extern "C" void rocket_free_kernels(rocket_kernels *h)
+{
+    if (!h) return;
+    if (h->d_blob) {
+        int cur = -1;
+        if (hipGetDevice(&cur) == hipSuccess && cur != h->device && hipSetDevice(h->device) == hipSuccess) {
+            (void)hipFree(h->d_blob);
+            (void)hipSetDevice(cur);
+        } else {
+            (void)hipFree(h->d_blob);
+        }
+    }
+    delete h;
+}
+
+// workspace layout: [padded batch: B*C*row_len floats][backward: B*(total_w + 2K) floats]
+static size_t padded_batch_bytes(const rocket_kernels *h, int32_t B)
+{
+    return static_cast<size_t>(round_up(static_cast<int64_t>(B) * h->C * h->row_len * 4, 256));
+}
+
+static size_t backward_partial_floats(const rocket_kernels *h) { return static_cast<size_t>(h->w_off[h->K]) + h->K; }
+
+extern "C" size_t rocket_workspace_bytes(const rocket_kernels *h, int32_t B, uint32_t mask, int backward)
+{
+    if (!h || B < 1 || rocket_num_features(mask) == 0) return 0;
+    size_t bytes = padded_batch_bytes(h, B);
+    if (backward) bytes += static_cast<size_t>(B) * backward_partial_floats(h) * 4;
+    return bytes;
+}
+
+// ------------------------------------------------------------------ device mirror
+
+static int ensure_device(rocket_kernels *h, hipStream_t stream)
+{
+    int cur = 0;
+    RK_HIP(hipGetDevice(&cur));
+    const int32_t K = h->K;
+    const size_t rec_b = round_up(static_cast<int64_t>(K) * sizeof(RkKernelRec), 256);
+    const size_t ord_b = round_up(static_cast<int64_t>(K) * 4, 256);
+    const size_t ch_b = round_up(static_cast<int64_t>(h->channels.size()) * 4, 256);
+    const size_t w_b = round_up(static_cast<int64_t>(h->weights.size()) * 4, 256);
+    if (h->d_blob && h->device != cur)
+        return rk_fail(ROCKET_EINVAL, "handle was first used on another device");
+    if (!h->d_blob) {
+        h->blob_bytes = rec_b + ord_b + ch_b + w_b;
+        RK_HIP(hipMalloc(&h->d_blob, h->blob_bytes));
+        h->device = cur;
+        char *base = static_cast<char *>(h->d_blob);
+        h->d_rec = reinterpret_cast<const RkKernelRec *>(base);
+        h->d_order = reinterpret_cast<const int32_t *>(base + rec_b);
+        h->d_channels = reinterpret_cast<const int32_t *>(base + rec_b + ord_b);
+        h->d_weights = reinterpret_cast<float *>(base + rec_b + ord_b + ch_b);
+        h->params_dirty = true;
+    }
+    if (h->params_dirty) {
+        std::vector<RkKernelRec> rec(K);
+        for (int32_t k = 0; k < K; ++k) {
+            RkKernelRec &r = rec[k];
+            r.len = h->length[k]; r.dil = h->dilation[k]; r.pad = h->padding[k];
+            r.nout = h->L + 2 * h->padding[k] - (h->length[k] - 1) * h->dilation[k];
+            r.bias = h->bias[k]; r.nch = h->n_ch[k];
+            r.ch_off = static_cast<int32_t>(h->ch_off[k]);
+            r.w_off = static_cast<int32_t>(h->w_off[k]);
+        }
+        // pageable sources: these copies return once the source has been read
+        RK_HIP(hipMemcpyAsync(const_cast<RkKernelRec *>(h->d_rec), rec.data(), K * sizeof(RkKernelRec), hipMemcpyHostToDevice, stream));
+        RK_HIP(hipMemcpyAsync(const_cast<int32_t *>(h->d_order), h->order.data(), K * 4, hipMemcpyHostToDevice, stream));
+        RK_HIP(hipMemcpyAsync(const_cast<int32_t *>(h->d_channels), h->channels.data(), h->channels.size() * 4, hipMemcpyHostToDevice, stream));
+        RK_HIP(hipMemcpyAsync(h->d_weights, h->weights.data(), h->weights.size() * 4, hipMemcpyHostToDevice, stream));
+        RK_HIP(hipStreamSynchronize(stream));
+        h->params_dirty = false;
+    }
+    return ROCKET_OK;
+}
+
+// ------------------------------------------------------------------ kernels
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr float kLog2e = 1.4426950408889634f;
+
+// Copies B*C rows of L floats into rows of row_len floats: `lead` zeros, the
+// samples, zeros to the end.  One thread writes four consecutive floats.
+__global__ __launch_bounds__(256) void rk_pad_rows(const float *__restrict__ x, float *__restrict__ xpad,
+                                                   int L, int lead, int row_len, int nrows)
+{
+    const int col = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (col >= row_len) return;
+    for (int row = blockIdx.y; row < nrows; row += gridDim.y) {
+        const float *src = x + static_cast<size_t>(row) * L;
+        float4 v;
+        const int s = col - lead;
+        v.x = (s >= 0 && s < L) ? src[s] : 0.f;
+        v.y = (s + 1 >= 0 && s + 1 < L) ? src[s + 1] : 0.f;
+        v.z = (s + 2 >= 0 && s + 2 < L) ? src[s + 2] : 0.f;
+        v.w = (s + 3 >= 0 && s + 3 < L) ? src[s + 3] : 0.f;
+        *reinterpret_cast<float4 *>(xpad + static_cast<size_t>(row) * row_len + col) = v;
+    }
+}
+
+struct PoolState {
+    float vmax;   // per lane
+    float ssum;   // per lane
+    int cnt;      // wavefront-uniform: positives seen by this wavefront
+};
+
+// Raw buffer descriptor (stride 0, 32-bit data format) over `bytes` bytes at `base`.
+// Buffer loads take the address as descriptor base + scalar offset + lane offset,
+// so the walk along a strip costs scalar adds only; reads past `bytes` return 0.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rk_row_buffer(const char *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0, static_cast<int>(bytes), 0x00020000);
+}
+
+// R conv outputs of one strip: acc[i] = y[t0 + i*d].  `xk` points at the padded
+// row of channel 0 shifted by -p, so x[c][t - p] is the float at xk + c*row_bytes + 4t.
+template <int LEN, int R>
+__device__ __forceinline__ void rk_strip_conv(const char *__restrict__ xk, size_t row_bytes, uint32_t span_bytes,
+                                              uint32_t dbytes, uint32_t voff, int nch,
+                                              const int32_t *__restrict__ chans, const float *__restrict__ wts,
+                                              float bias, float (&acc)[R])
+{
+#pragma unroll
+    for (int i = 0; i < R; ++i) acc[i] = bias;
+    for (int c = 0; c < nch; ++c) {
+        const __amdgpu_buffer_rsrc_t row = rk_row_buffer(xk + static_cast<size_t>(chans[c]) * row_bytes, span_bytes);
+        float w[LEN];
+#pragma unroll
+        for (int j = 0; j < LEN; ++j) w[j] = wts[c * LEN + j];
+#pragma unroll
+        for (int i = 0; i < R + LEN - 1; ++i) {
+            const float xv = __builtin_bit_cast(
+                float, __builtin_amdgcn_raw_buffer_load_b32(row, static_cast<int>(voff), static_cast<int>(i * dbytes), 0));
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) {
+                const int o = i - j;
+                if (o >= 0 && o < R) acc[o] = fmaf(w[j], xv, acc[o]);
+            }
+        }
+    }
+}
+
+template <int R, int MASK>
+__device__ __forceinline__ void rk_pool(const float (&acc)[R], float nl, float ns, PoolState &st)
+{
+    if (MASK & ROCKET_F_MAX) {
+#pragma unroll
+        for (int i = 0; i < R; ++i) st.vmax = fmaxf(st.vmax, acc[i]);
+    }
+    if (MASK & ROCKET_F_PPV) {
+#pragma unroll
+        for (int i = 0; i < R; ++i) st.cnt += __builtin_popcountll(__ballot(acc[i] > 0.f));
+    }
+    if (MASK & ROCKET_F_SOFTPPV) {
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            // 1/(1+exp(-(lambda*y+shift))) with nl = -lambda*log2(e), ns = -shift*log2(e)
+            const float e = __builtin_amdgcn_exp2f(fmaf(acc[i], nl, ns));
+            st.ssum += __builtin_amdgcn_rcpf(1.f + e);
+        }
+    }
+}
+
+// All strips of `nbands` bands of R rows x `ncols` columns starting at row `row0`.
+template <int LEN, int R, int MASK>
+__device__ __forceinline__ void rk_segment(const char *__restrict__ xk, size_t row_bytes, uint32_t span_bytes, int d, int row0,
+                                           int nbands, int ncols, int nch, const int32_t *__restrict__ chans,
+                                           const float *__restrict__ wts, float bias, float nl, float ns,
+                                           PoolState &st)
+{
+    const int nstrips = nbands * ncols;
+    const uint32_t dbytes = static_cast<uint32_t>(d) * 4u;
+    for (int base = 0; base < nstrips; base += kThreads) {
+        const int s = base + static_cast<int>(threadIdx.x);
+        if (s < nstrips) {
+            const int band = (nbands == 1) ? 0 : s / ncols;
+            const int r = s - band * ncols;
+            const uint32_t voff = static_cast<uint32_t>((row0 + band * R) * d + r) * 4u;
+            float acc[R];
+            rk_strip_conv<LEN, R>(xk, row_bytes, span_bytes, dbytes, voff, nch, chans, wts, bias, acc);
+            rk_pool<R, MASK>(acc, nl, ns, st);
+        }
+    }
+}
+
+template <int LEN, int MASK>
+__device__ __forceinline__ void rk_forward_body(const RkKernelRec rec, const char *__restrict__ xk, size_t row_bytes, uint32_t span_bytes,
+                                                const int32_t *__restrict__ chans, const float *__restrict__ wts,
+                                                float nl, float ns, PoolState &st)
+{
+    const int d = rec.dil;
+    const int rows = rec.nout / d;            // full rows of d outputs
+    const int tail = rec.nout - rows * d;     // outputs of the partial last row
+    int row0 = 0;
+    const int nb16 = rows >> 4;
+    if (nb16) rk_segment<LEN, 16, MASK>(xk, row_bytes, span_bytes, d, 0, nb16, d, rec.nch, chans, wts, rec.bias, nl, ns, st);
+    row0 = nb16 << 4;
+    if (rows & 8) { rk_segment<LEN, 8, MASK>(xk, row_bytes, span_bytes, d, row0, 1, d, rec.nch, chans, wts, rec.bias, nl, ns, st); row0 += 8; }
+    if (rows & 4) { rk_segment<LEN, 4, MASK>(xk, row_bytes, span_bytes, d, row0, 1, d, rec.nch, chans, wts, rec.bias, nl, ns, st); row0 += 4; }
+    if (rows & 2) { rk_segment<LEN, 2, MASK>(xk, row_bytes, span_bytes, d, row0, 1, d, rec.nch, chans, wts, rec.bias, nl, ns, st); row0 += 2; }
+    if (rows & 1) { rk_segment<LEN, 1, MASK>(xk, row_bytes, span_bytes, d, row0, 1, d, rec.nch, chans, wts, rec.bias, nl, ns, st); row0 += 1; }
+    if (tail) rk_segment<LEN, 1, MASK>(xk, row_bytes, span_bytes, d, row0, 1, tail, rec.nch, chans, wts, rec.bias, nl, ns, st);
+}
+
+// grid: B*K workgroups; workgroup g handles series g / K and kernel order[g % K].
+template <int MASK>
+__global__ __launch_bounds__(kThreads) void rk_forward(const float *__restrict__ xpad, int row_len, int lead, int C, int K,
+                                                       const RkKernelRec *__restrict__ recs,
+                                                       const int32_t *__restrict__ order,
+                                                       const int32_t *__restrict__ channels,
+                                                       const float *__restrict__ weights, float nl, float ns,
+                                                       float *__restrict__ out)
+{
+    const int b = blockIdx.x / K;
+    const int k = order[blockIdx.x - b * K];
+    const RkKernelRec rec = recs[k];
+    const size_t row_bytes = static_cast<size_t>(row_len) * 4;
+    const char *xk = reinterpret_cast<const char *>(xpad) + static_cast<size_t>(b) * C * row_bytes +
+                     static_cast<size_t>(lead - rec.pad) * 4;
+    // bytes from the shifted row start to the end of the padded row
+    const uint32_t span_bytes = static_cast<uint32_t>(row_len - (lead - rec.pad)) * 4u;
+    const int32_t *chans = channels + rec.ch_off;
+    const float *wts = weights + rec.w_off;
+
+    PoolState st;
+    st.vmax = -INFINITY;
+    st.ssum = 0.f;
+    st.cnt = 0;
+    if (rec.len == 7) rk_forward_body<7, MASK>(rec, xk, row_bytes, span_bytes, chans, wts, nl, ns, st);
+    else if (rec.len == 9) rk_forward_body<9, MASK>(rec, xk, row_bytes, span_bytes, chans, wts, nl, ns, st);
+    else rk_forward_body<11, MASK>(rec, xk, row_bytes, span_bytes, chans, wts, nl, ns, st);
+
+    // close the reductions: lanes -> wavefront (shuffles) -> workgroup (LDS)
+    float vmax = st.vmax, ssum = st.ssum;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        vmax = fmaxf(vmax, __shfl_xor(vmax, off));
+        ssum += __shfl_xor(ssum, off);
+    }
+    __shared__ float s_max[kWaves];
+    __shared__ float s_sum[kWaves];
+    __shared__ int s_cnt[kWaves];
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { s_max[wave] = vmax; s_sum[wave] = ssum; s_cnt[wave] = st.cnt; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float m = s_max[0], sm = s_sum[0];
+        int cn = s_cnt[0];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) { m = fmaxf(m, s_max[w]); sm += s_sum[w]; cn += s_cnt[w]; }
+        constexpr int F = ((MASK & 1) ? 1 : 0) + ((MASK & 2) ? 1 : 0) + ((MASK & 4) ? 1 : 0);
+        float *o = out + static_cast<size_t>(b) * F * K + k;
+        int f = 0;
+        if (MASK & ROCKET_F_MAX) { o[static_cast<size_t>(f) * K] = m; ++f; }
+        if (MASK & ROCKET_F_PPV) { o[static_cast<size_t>(f) * K] = static_cast<float>(static_cast<double>(cn) / static_cast<double>(rec.nout)); ++f; }
+        if (MASK & ROCKET_F_SOFTPPV) { o[static_cast<size_t>(f) * K] = sm / static_cast<float>(rec.nout); ++f; }
+    }
+}
+
+// ------------------------------------------------------------------ launches
+
+static int check_common(const char *fn, const rocket_kernels *h, const void *x, int32_t B, uint32_t mask,
+                        float lambda, float shift, const void *ws, size_t ws_bytes, int backward)
+{
+    const std::string who(fn);
+    if (!h) return rk_fail(ROCKET_EINVAL, who + ": NULL handle");
+    if (!x) return rk_fail(ROCKET_EINVAL, who + ": x_dev is NULL");
+    if (B < 1) return rk_fail(ROCKET_EINVAL, who + ": B must be >= 1");
+    if (rocket_num_features(mask) == 0) return rk_fail(ROCKET_EINVAL, who + ": feature mask must be a non-empty subset of 7");
+    if (!std::isfinite(lambda) || !std::isfinite(shift)) return rk_fail(ROCKET_EINVAL, who + ": lambda and shift must be finite");
+    if (static_cast<int64_t>(B) * h->K > INT32_MAX) return rk_fail(ROCKET_EINVAL, who + ": B*K exceeds the grid limit");
+    const size_t need = rocket_workspace_bytes(h, B, mask, backward);
+    if (!ws || ws_bytes < need)
+        return rk_fail(ROCKET_EWORKSPACE, who + ": workspace of " + std::to_string(need) + " bytes required");
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return rk_fail(ROCKET_EWORKSPACE, who + ": workspace must be 256-byte aligned");
+    return ROCKET_OK;
+}
+
+static int launch_pad(const rocket_kernels *h, const float *x, int32_t B, float *xpad, hipStream_t stream)
+{
+    const int nrows = B * h->C;
+    dim3 grid(static_cast<unsigned>((h->row_len / 4 + 255) / 256), static_cast<unsigned>(std::min(nrows, 32768)));
+    hipLaunchKernelGGL(rk_pad_rows, grid, dim3(256), 0, stream, x, xpad, h->L, h->lead,
+                       static_cast<int>(h->row_len), nrows);
+    RK_HIP(hipGetLastError());
+    return ROCKET_OK;
+}
+
+template <int MASK>
+static void launch_forward(const rocket_kernels *h, const float *xpad, int32_t B, float nl, float ns, float *out,
+                           hipStream_t stream)
+{
+    hipLaunchKernelGGL(rk_forward<MASK>, dim3(static_cast<unsigned>(B) * h->K), dim3(kThreads), 0, stream, xpad,
+                       static_cast<int>(h->row_len), h->lead, h->C, h->K, h->d_rec, h->d_order, h->d_channels,
+                       h->d_weights, nl, ns, out);
+}
+
+extern "C" int rocket_transform(rocket_kernels *h, const float *x_dev, int32_t B, uint32_t mask, float lambda,
+                                float shift, float *out_dev, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_common("rocket_transform", h, x_dev, B, mask, lambda, shift, ws, ws_bytes, 0);
+    if (rc != ROCKET_OK) return rc;
+    if (!out_dev) return rk_fail(ROCKET_EINVAL, "rocket_transform: out_dev is NULL");
+    if (h->row_len > INT32_MAX) return rk_fail(ROCKET_EINVAL, "rocket_transform: series too long");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    rc = ensure_device(h, stream);
+    if (rc != ROCKET_OK) return rc;
+    float *xpad = static_cast<float *>(ws);
+    rc = launch_pad(h, x_dev, B, xpad, stream);
+    if (rc != ROCKET_OK) return rc;
+    const float nl = -lambda * kLog2e, ns = -shift * kLog2e;
+    switch (mask) {
+        case 1: launch_forward<1>(h, xpad, B, nl, ns, out_dev, stream); break;
+        case 2: launch_forward<2>(h, xpad, B, nl, ns, out_dev, stream); break;
+        case 3: launch_forward<3>(h, xpad, B, nl, ns, out_dev, stream); break;
+        case 4: launch_forward<4>(h, xpad, B, nl, ns, out_dev, stream); break;
+        case 5: launch_forward<5>(h, xpad, B, nl, ns, out_dev, stream); break;
+        case 6: launch_forward<6>(h, xpad, B, nl, ns, out_dev, stream); break;
+        default: launch_forward<7>(h, xpad, B, nl, ns, out_dev, stream); break;
+    }
+    RK_HIP(hipGetLastError());
+    return ROCKET_OK;
+}
+
+extern "C" int rocket_soft_ppv_backward(rocket_kernels *h, const float *x_dev, int32_t B, uint32_t mask,
+                                        const float *grad_out_dev, float lambda, float shift, int include_max,
+                                        float *grad_w_dev, float *grad_b_dev, void *ws, size_t ws_bytes,
+                                        void *hip_stream)
+{
+    int rc = check_common("rocket_soft_ppv_backward", h, x_dev, B, mask, lambda, shift, ws, ws_bytes, 1);
+    if (rc != ROCKET_OK) return rc;
+    if (!(mask & ROCKET_F_SOFTPPV)) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: mask must contain ROCKET_F_SOFTPPV");
+    if (include_max && !(mask & ROCKET_F_MAX)) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: include_max needs ROCKET_F_MAX in the mask");
+    if (!grad_out_dev || !grad_w_dev || !grad_b_dev) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: NULL gradient pointer");
+    (void)hip_stream;
+    return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: not built yet");
+}

@@ -1,0 +1,49 @@
+// Internal declarations shared by the host sampler and the HIP translation unit.
+#pragma once
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "rocket.h"
+
+// One packed record per kernel as the device code reads it (32 bytes).
+struct RkKernelRec {
+    int32_t len, dil, pad, nout;
+    float bias;
+    int32_t nch;
+    int32_t ch_off;  // into channels[]
+    int32_t w_off;   // into weights[]
+};
+
+struct rocket_kernels {
+    int32_t K = 0, C = 0, L = 0;
+    std::vector<int32_t> length, dilation, padding, n_ch, channels;
+    std::vector<float> bias, weights;
+    std::vector<int64_t> ch_off, w_off;
+
+    // plan: kernels in launch order (most expensive first), padded row geometry
+    std::vector<int32_t> order;
+    int32_t pad_max = 0;     // largest padding of any kernel
+    int32_t lead = 0;        // zeros in front of every padded row (multiple of 64)
+    int64_t row_len = 0;     // floats per padded row (multiple of 64)
+    double conv_fma = 0.0;   // sum_k n_k * n_ch_k * len_k
+    double outputs = 0.0;    // sum_k n_k
+
+    // device mirror (allocated on first use on `device`)
+    int device = -1;
+    void *d_blob = nullptr;
+    size_t blob_bytes = 0;
+    bool params_dirty = true;
+    const RkKernelRec *d_rec = nullptr;
+    const int32_t *d_order = nullptr;
+    const int32_t *d_channels = nullptr;
+    float *d_weights = nullptr;
+};
+
+void rk_set_error(const std::string &msg);
+int rk_fail(int code, const std::string &msg);
+
+// sampler.cpp: fills the per-kernel arrays of `h` (K, C, L already set)
+void rk_sample_kernels(uint64_t seed, rocket_kernels &h);
+// plan.cpp part: offsets, launch order, padded row geometry; returns ROCKET_OK or an error
+int rk_finish_handle(rocket_kernels &h);

@@ -1,0 +1,101 @@
+// Random kernel initialisation (paper section 3.1), host side of the library.
+//
+// Compiled with -ffp-contract=off and without fast-math: every kernel must come
+// out bit-identical on any host.  The draws of one kernel come from its own
+// SplitMix64 stream keyed by (seed, kernel index); each draw uses one 64-bit
+// output.  Order of draws: length, channel count, channel subset, weights
+// (channel by channel), bias, dilation, padding.
+#include <cmath>
+#include <numeric>
+
+#include "rocket_internal.hpp"
+
+namespace {
+
+constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;
+
+inline uint64_t scramble(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+class KernelStream {
+public:
+    KernelStream(uint64_t seed, uint64_t k)
+        : state_(scramble(scramble(seed + kGolden) + (k + 1) * kGolden)) {}
+    uint64_t bits() { state_ += kGolden; return scramble(state_); }
+    uint32_t word() { return static_cast<uint32_t>(bits() >> 32); }
+    // uniform on [0,1) and on (0,1], 53 bits
+    double unit() { return static_cast<double>(bits() >> 11) * 0x1.0p-53; }
+    double unit_open() { return static_cast<double>((bits() >> 11) + 1) * 0x1.0p-53; }
+    // integer uniform on [0, range) by the multiply-shift map
+    uint32_t below(uint32_t range) { return static_cast<uint32_t>((static_cast<uint64_t>(word()) * range) >> 32); }
+
+    // N(0,1) by the ratio of uniforms: the point (u, v) is uniform on
+    // (0,1] x [-sqrt(2/e), sqrt(2/e)); v/u is kept when (v/u)^2 <= -4 ln u.
+    double gauss()
+    {
+        for (;;) {
+            const double u = unit_open();
+            const double v = 0.8577638849607068 * (2.0 * unit() - 1.0);
+            const double ratio = v / u;
+            if (ratio * ratio <= -4.0 * std::log(u)) return ratio;
+        }
+    }
+
+private:
+    uint64_t state_;
+};
+
+}  // namespace
+
+void rk_sample_kernels(uint64_t seed, rocket_kernels &h)
+{
+    const int32_t K = h.K, C = h.C, L = h.L;
+    h.length.resize(K); h.dilation.resize(K); h.padding.resize(K);
+    h.n_ch.resize(K); h.bias.resize(K);
+    h.channels.clear(); h.weights.clear();
+    const int32_t max_ch = C < 9 ? C : 9;
+    const double ch_span = std::log2(static_cast<double>(max_ch + 1));
+    std::vector<int32_t> pool(C);
+    std::vector<double> row(11);
+
+    for (int32_t k = 0; k < K; ++k) {
+        KernelStream rng(seed, static_cast<uint64_t>(k));
+        const int32_t len = 7 + 2 * static_cast<int32_t>(rng.below(3));
+
+        int32_t nch = static_cast<int32_t>(std::floor(std::exp2(rng.unit() * ch_span)));
+        if (nch < 1) nch = 1;
+        if (nch > max_ch) nch = max_ch;
+
+        std::iota(pool.begin(), pool.end(), 0);
+        for (int32_t i = 0; i < nch; ++i) {
+            const int32_t j = i + static_cast<int32_t>(rng.below(static_cast<uint32_t>(C - i)));
+            std::swap(pool[i], pool[j]);
+            h.channels.push_back(pool[i]);
+        }
+
+        for (int32_t c = 0; c < nch; ++c) {
+            double total = 0.0;
+            for (int32_t j = 0; j < len; ++j) { row[j] = rng.gauss(); total += row[j]; }
+            const double mean = total / static_cast<double>(len);
+            for (int32_t j = 0; j < len; ++j) h.weights.push_back(static_cast<float>(row[j] - mean));
+        }
+
+        h.bias[k] = static_cast<float>(static_cast<double>(rng.word() >> 8) * 0x1.0p-23 - 1.0);
+
+        const double span = std::log2(static_cast<double>(L - 1) / static_cast<double>(len - 1));
+        int32_t dil = static_cast<int32_t>(std::floor(std::exp2(rng.unit() * span)));
+        const int32_t dil_max = (L - 1) / (len - 1);
+        if (dil < 1) dil = 1;
+        if (dil > dil_max) dil = dil_max;
+
+        const bool same = (rng.word() & 1u) != 0;
+        h.length[k] = len;
+        h.n_ch[k] = nch;
+        h.dilation[k] = dil;
+        h.padding[k] = same ? ((len - 1) * dil) / 2 : 0;
+    }
+}

@@ -1,0 +1,236 @@
+"""Python binding of librocket_mi355x.so (include/rocket.h), same names as the C ABI.
+
+Argument marshalling only: every step of the transform runs in the HIP
+library.  torch supplies device memory and the current stream.  There is no
+CPU fallback: importing works without a GPU (kernel sampling is host code),
+but the compute calls need the library and a device and fail loudly otherwise.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+ROCKET_F_MAX, ROCKET_F_PPV, ROCKET_F_SOFTPPV = 1, 2, 4
+ROCKET_OK, ROCKET_EINVAL, ROCKET_ENOMEM, ROCKET_EHIP, ROCKET_ESHAPE, ROCKET_EWORKSPACE = 0, -1, -2, -3, -4, -5
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librocket_mi355x.so")
+
+EXPORTS = [
+    "rocket_make_kernels", "rocket_kernels_import", "rocket_kernels_view_get",
+    "rocket_kernels_set_params", "rocket_num_features", "rocket_workspace_bytes",
+    "rocket_transform", "rocket_soft_ppv_backward", "rocket_work_per_series",
+    "rocket_free_kernels", "rocket_last_error",
+]
+
+
+class RocketError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__("rocket error %d: %s" % (code, message))
+        self.code = code
+
+
+class _View(C.Structure):
+    _fields_ = [
+        ("K", C.c_int32), ("C", C.c_int32), ("L", C.c_int32),
+        ("total_channels", C.c_int64), ("total_weights", C.c_int64),
+        ("length", C.POINTER(C.c_int32)), ("dilation", C.POINTER(C.c_int32)),
+        ("padding", C.POINTER(C.c_int32)), ("n_ch", C.POINTER(C.c_int32)),
+        ("bias", C.POINTER(C.c_float)),
+        ("ch_off", C.POINTER(C.c_int64)), ("w_off", C.POINTER(C.c_int64)),
+        ("channels", C.POINTER(C.c_int32)), ("weights", C.POINTER(C.c_float)),
+    ]
+
+
+_lib = None
+
+
+def load_library():
+    """Loads the in-tree library; builds it first only if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, u32, u64, f32 = C.c_void_p, C.c_int32, C.c_uint32, C.c_uint64, C.c_float
+    lib.rocket_make_kernels.argtypes = [u64, i32, i32, i32, C.POINTER(vp)]
+    lib.rocket_kernels_import.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, C.POINTER(vp)]
+    lib.rocket_kernels_view_get.argtypes = [vp, C.POINTER(_View)]
+    lib.rocket_kernels_set_params.argtypes = [vp, vp, vp]
+    lib.rocket_num_features.argtypes = [u32]
+    lib.rocket_num_features.restype = i32
+    lib.rocket_workspace_bytes.argtypes = [vp, i32, u32, C.c_int]
+    lib.rocket_workspace_bytes.restype = C.c_size_t
+    lib.rocket_transform.argtypes = [vp, vp, i32, u32, f32, f32, vp, vp, C.c_size_t, vp]
+    lib.rocket_soft_ppv_backward.argtypes = [vp, vp, i32, u32, vp, f32, f32, C.c_int, vp, vp, vp, C.c_size_t, vp]
+    lib.rocket_work_per_series.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.rocket_free_kernels.argtypes = [vp]
+    lib.rocket_free_kernels.restype = None
+    lib.rocket_last_error.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def rocket_last_error():
+    return load_library().rocket_last_error().decode()
+
+
+def _check(rc):
+    if rc != ROCKET_OK:
+        raise RocketError(rc, rocket_last_error())
+
+
+def rocket_num_features(mask):
+    return int(load_library().rocket_num_features(mask))
+
+
+class Kernels:
+    """Owns a rocket_kernels handle."""
+
+    def __init__(self, handle):
+        self._h = C.c_void_p(handle)
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise RocketError(ROCKET_EINVAL, "kernels already freed")
+        return self._h
+
+    def free(self):
+        if self._h:
+            load_library().rocket_free_kernels(self._h)
+            self._h = C.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def rocket_make_kernels(seed, K, C_, L):
+    out = C.c_void_p()
+    _check(load_library().rocket_make_kernels(seed, K, C_, L, C.byref(out)))
+    return Kernels(out.value)
+
+
+def _np(a, dt):
+    return np.ascontiguousarray(a, dtype=dt)
+
+
+def rocket_kernels_import(K, C_, L, length, dilation, padding, bias, n_ch, channels, weights):
+    arrs = [_np(length, np.int32), _np(dilation, np.int32), _np(padding, np.int32), _np(bias, np.float32),
+            _np(n_ch, np.int32), _np(channels, np.int32), _np(weights, np.float32)]
+    out = C.c_void_p()
+    _check(load_library().rocket_kernels_import(K, C_, L, *[a.ctypes.data for a in arrs], C.byref(out)))
+    return Kernels(out.value)
+
+
+def rocket_kernels_view_get(kernels):
+    """Copies of the handle's arrays, keyed like the C struct."""
+    v = _View()
+    _check(load_library().rocket_kernels_view_get(kernels.handle, C.byref(v)))
+    K = v.K
+
+    def arr(ptr, n, dt):
+        return np.ctypeslib.as_array(ptr, shape=(n,)).astype(dt, copy=True) if n else np.zeros(0, dt)
+
+    return {
+        "K": K, "C": v.C, "L": v.L,
+        "length": arr(v.length, K, np.int32), "dilation": arr(v.dilation, K, np.int32),
+        "padding": arr(v.padding, K, np.int32), "n_ch": arr(v.n_ch, K, np.int32),
+        "bias": arr(v.bias, K, np.float32),
+        "ch_off": arr(v.ch_off, K + 1, np.int64), "w_off": arr(v.w_off, K + 1, np.int64),
+        "channels": arr(v.channels, v.total_channels, np.int32),
+        "weights": arr(v.weights, v.total_weights, np.float32),
+    }
+
+
+def rocket_kernels_set_params(kernels, weights=None, bias=None):
+    w = None if weights is None else _np(weights, np.float32)
+    b = None if bias is None else _np(bias, np.float32)
+    _check(load_library().rocket_kernels_set_params(
+        kernels.handle, None if w is None else w.ctypes.data, None if b is None else b.ctypes.data))
+
+
+def rocket_workspace_bytes(kernels, B, feature_mask, backward=False):
+    return int(load_library().rocket_workspace_bytes(kernels.handle, B, feature_mask, int(bool(backward))))
+
+
+def rocket_work_per_series(kernels):
+    fma, outs = C.c_double(), C.c_double()
+    _check(load_library().rocket_work_per_series(kernels.handle, C.byref(fma), C.byref(outs)))
+    return fma.value, outs.value
+
+
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        raise RocketError(ROCKET_EHIP, "no GPU visible: the transform has no CPU path")
+    return torch
+
+
+def _stream_ptr(torch, stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _workspace(torch, kernels, B, mask, backward, workspace, device):
+    need = rocket_workspace_bytes(kernels, B, mask, backward)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    return workspace, need
+
+
+def rocket_transform(kernels, x, feature_mask, lam=10.0, shift=-3.0, out=None, workspace=None, stream=None):
+    """x: float32 CUDA tensor (B, C, L), contiguous.  Returns out (B, F*K)."""
+    torch = _torch()
+    if not (x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() == 3):
+        raise RocketError(ROCKET_EINVAL, "x must be a contiguous float32 CUDA tensor of shape (B, C, L)")
+    v = _View()
+    _check(load_library().rocket_kernels_view_get(kernels.handle, C.byref(v)))
+    B = x.shape[0]
+    if x.shape[1] != v.C or x.shape[2] != v.L:
+        raise RocketError(ROCKET_ESHAPE, "x is (B, %d, %d) but the kernels were made for (%d, %d)"
+                          % (x.shape[1], x.shape[2], v.C, v.L))
+    F = rocket_num_features(feature_mask)
+    if out is None:
+        out = torch.empty((B, max(F, 1) * v.K), dtype=torch.float32, device=x.device)
+    workspace, _ = _workspace(torch, kernels, B, feature_mask, False, workspace, x.device)
+    _check(load_library().rocket_transform(
+        kernels.handle, x.data_ptr(), B, feature_mask, lam, shift, out.data_ptr(),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(torch, stream)))
+    return out
+
+
+def rocket_soft_ppv_backward(kernels, x, feature_mask, grad_out, lam=10.0, shift=-3.0, include_max=False,
+                             grad_w=None, grad_b=None, workspace=None, stream=None):
+    """Returns (grad_w [total_weights], grad_b [K]) as float32 CUDA tensors."""
+    torch = _torch()
+    for t, name in ((x, "x"), (grad_out, "grad_out")):
+        if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+            raise RocketError(ROCKET_EINVAL, name + " must be a contiguous float32 CUDA tensor")
+    v = _View()
+    _check(load_library().rocket_kernels_view_get(kernels.handle, C.byref(v)))
+    B = x.shape[0]
+    if x.dim() != 3 or x.shape[1] != v.C or x.shape[2] != v.L:
+        raise RocketError(ROCKET_ESHAPE, "x does not match the kernels' (C, L)")
+    F = rocket_num_features(feature_mask)
+    if tuple(grad_out.shape) != (B, F * v.K):
+        raise RocketError(ROCKET_ESHAPE, "grad_out must be (B, F*K)")
+    if grad_w is None:
+        grad_w = torch.empty(v.total_weights, dtype=torch.float32, device=x.device)
+    if grad_b is None:
+        grad_b = torch.empty(v.K, dtype=torch.float32, device=x.device)
+    workspace, _ = _workspace(torch, kernels, B, feature_mask, True, workspace, x.device)
+    _check(load_library().rocket_soft_ppv_backward(
+        kernels.handle, x.data_ptr(), B, feature_mask, grad_out.data_ptr(), lam, shift, int(bool(include_max)),
+        grad_w.data_ptr(), grad_b.data_ptr(), workspace.data_ptr(),
+        workspace.numel() * workspace.element_size(), _stream_ptr(torch, stream)))
+    return grad_w, grad_b
+
+
+def rocket_free_kernels(kernels):
+    kernels.free()

@@ -1,0 +1,171 @@
+"""GPU parity of rocket_transform against the CPU oracle (needs an MI355X).
+Every call goes through the C ABI; inputs are the seeded workloads."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2301_08527_amd import rocket, synth
+from parity import check_forward, planes
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu(x):
+    import torch
+    return torch.from_numpy(x).cuda()
+
+
+def _run(h, x, mask, lam=10.0, shift=-3.0):
+    import torch
+    out = rocket.rocket_transform(h, _gpu(x), mask, lam, shift)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def _kernels(i, K=None):
+    cfg = synth.CONFIGS[i]
+    K = cfg["K"] if K is None else K
+    h = rocket.rocket_make_kernels(synth.seed_k(i), K, cfg["C"], cfg["L"])
+    return h, rocket.rocket_kernels_view_get(h)
+
+
+def test_config0_all_masks():
+    """univariate tiny, every kernel and series, every feature mask"""
+    cfg = synth.CONFIGS[0]
+    x = synth.make_input(0)
+    h, kr = _kernels(0)
+    for mask in range(1, 8):
+        print("config0 mask", mask, flush=True)
+        out = _run(h, x, mask)
+        assert out.shape == (cfg["B"], rocket.rocket_num_features(mask) * cfg["K"])
+        check_forward(x, kr, out, mask)
+
+
+def test_config1_univariate_standard():
+    """B=256, L=1000, K=10,000, all three features; every series and kernel"""
+    cfg = synth.CONFIGS[1]
+    x = synth.make_input(1)
+    h, kr = _kernels(1)
+    print("config1 run", flush=True)
+    out = _run(h, x, cfg["features"])
+    check_forward(x, kr, out, cfg["features"])
+
+
+def test_config2_multivariate_full_size():
+    """B=64 x 20 x 50,000, K=10,000 in the launch shape the benchmark times;
+    the oracle checks every series on a dilation-stratified kernel sample."""
+    cfg = synth.CONFIGS[2]
+    x = synth.make_input(2)
+    h, kr = _kernels(2)
+    print("config2 run", flush=True)
+    out = _run(h, x, cfg["features"])
+    sel = synth.pick_kernels(kr, 256, seed=2)
+    check_forward(x, kr, out, cfg["features"], sel=sel)
+    # properties that hold for every output
+    pl = planes(out.astype(np.float64), cfg["features"], cfg["K"])
+    assert np.all((pl["ppv"] >= 0) & (pl["ppv"] <= 1)) and np.all(np.isfinite(pl["max"]))
+
+
+def test_config4_long_series_with_spikes():
+    """B=8 x 20 x 200,000, K=20,000 (dilations up to ~33,000), all features"""
+    cfg = synth.CONFIGS[4]
+    x = synth.make_input(4)
+    h, kr = _kernels(4)
+    print("config4 run", flush=True)
+    out = _run(h, x, cfg["features"])
+    sel = synth.pick_kernels(kr, 200, seed=4)
+    check_forward(x, kr, out, cfg["features"], sel=sel)
+
+
+@pytest.mark.parametrize("lam,shift", [(0.0, -3.0), (1.0, -3.0), (3.0, -3.0), (100.0, -3.0), (1e4, -3.0), (10.0, 3.0)])
+def test_lambda_and_shift_sweep(lam, shift):
+    rng = np.random.default_rng(21)
+    B, C, L, K = 5, 7, 3001, 300
+    x = rng.standard_normal((B, C, L)).astype(np.float32)
+    h = rocket.rocket_make_kernels(99, K, C, L)
+    kr = rocket.rocket_kernels_view_get(h)
+    out = _run(h, x, 7, lam, shift)
+    check_forward(x, kr, out, 7, lam=lam, shift=shift)
+
+
+@pytest.mark.parametrize("B,C,L,K", [(1, 1, 11, 40), (3, 2, 12, 40), (2, 9, 64, 100), (1, 20, 257, 150),
+                                     (2, 3, 1025, 120), (1, 12, 4099, 120)])
+def test_small_and_ragged_shapes(B, C, L, K):
+    """shortest legal series, lengths that are not multiples of any tile, one series"""
+    rng = np.random.default_rng(L)
+    x = rng.standard_normal((B, C, L)).astype(np.float32)
+    h = rocket.rocket_make_kernels(7, K, C, L)
+    kr = rocket.rocket_kernels_view_get(h)
+    out = _run(h, x, 7)
+    check_forward(x, kr, out, 7)
+
+
+def test_imported_extreme_kernels():
+    """hand-built kernels: every length at d=1 and at the largest dilation,
+    padded and not, single output position, nine channels"""
+    rng = np.random.default_rng(5)
+    C, L, B = 9, 2000, 3
+    specs = []
+    for ln in (7, 9, 11):
+        dmax = (L - 1) // (ln - 1)
+        for d in (1, 2, 3, 17, 63, 64, 65, 100, dmax - 1, dmax):
+            for padded in (False, True):
+                nch = int(rng.integers(1, 10))
+                specs.append((ln, d, padded, nch))
+    length = np.array([s[0] for s in specs], np.int32)
+    dil = np.array([s[1] for s in specs], np.int32)
+    pad = np.array([(s[0] - 1) * s[1] // 2 if s[2] else 0 for s in specs], np.int32)
+    nch = np.array([s[3] for s in specs], np.int32)
+    chans = np.concatenate([rng.permutation(C)[:m] for m in nch]).astype(np.int32)
+    w = rng.standard_normal(int((nch * length).sum())).astype(np.float32)
+    bias = rng.uniform(-1, 1, len(specs)).astype(np.float32)
+    h = rocket.rocket_kernels_import(len(specs), C, L, length, dil, pad, bias, nch, chans, w)
+    kr = rocket.rocket_kernels_view_get(h)
+    x = rng.standard_normal((B, C, L)).astype(np.float32)
+    out = _run(h, x, 7)
+    ref = check_forward(x, kr, out, 7)
+    assert ref["n_out"].min() <= 8      # some kernels have only a handful of positions
+
+
+def test_constant_series_closed_form():
+    """mean-centred weights: a constant series through unpadded kernels gives the bias"""
+    C, L, K = 4, 900, 200
+    x = np.repeat(np.array([0.5, -1.0, 2.0, 0.0], np.float32)[None, :, None], L, axis=2)
+    h = rocket.rocket_make_kernels(3, K, C, L)
+    kr = rocket.rocket_kernels_view_get(h)
+    out = planes(_run(h, x, 7).astype(np.float64), 7, K)
+    un = kr["padding"] == 0
+    b = kr["bias"].astype(np.float64)
+    assert np.all(np.abs(out["max"][0, un] - b[un]) < 1e-5)
+    clear = un & (np.abs(b) > 1e-4)
+    assert np.array_equal(out["ppv"][0, clear], (b[clear] > 0).astype(np.float64))
+    assert np.all(np.abs(out["softppv"][0, un] - 1 / (1 + np.exp(-(10 * b[un] - 3)))) < 1e-4)
+
+
+def test_outputs_are_overwritten_and_repeatable():
+    import torch
+    x = synth.make_input(0)
+    h, kr = _kernels(0)
+    xd = _gpu(x)
+    out = torch.full((16, 1000), float("nan"), device="cuda")
+    ws = torch.empty(rocket.rocket_workspace_bytes(h, 16, 3), dtype=torch.uint8, device="cuda")
+    ws.fill_(255)
+    rocket.rocket_transform(h, xd, 3, out=out, workspace=ws)
+    a = out.cpu().numpy().copy()
+    rocket.rocket_transform(h, xd, 3, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(a, out.cpu().numpy()) and np.all(np.isfinite(a))
+    # a side stream works as well
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        out2 = rocket.rocket_transform(h, xd, 3, workspace=ws, stream=s)
+    s.synchronize()
+    assert np.array_equal(a, out2.cpu().numpy())
+
+
+def test_shape_mismatch_is_an_error():
+    h, _ = _kernels(0)
+    with pytest.raises(rocket.RocketError):
+        rocket.rocket_transform(h, _gpu(np.zeros((2, 1, 500), np.float32)), 3)
+    with pytest.raises(rocket.RocketError):
+        rocket.rocket_transform(h, _gpu(np.zeros((2, 2, 512), np.float32)), 3)
