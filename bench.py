@@ -1,0 +1,154 @@
+#!/usr/bin/env python3
+"""Benchmark of the ROCKET transform hot path on one MI355X.
+
+A step is one rocket_transform call (zero-pad copy + conv/pooling kernel) on
+the paper's headline workload: a batch of 64 examples of 20 channels x 50,000
+timesteps through K = 10,000 random kernels, two pooled features per kernel
+(max + PPV).  Inputs are synthetic (seeded AR(1) channels, z-normalised) and
+resident in HBM before the timed region.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X datasheet, packed FP32 on the vector ALUs
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "rk_forward_hbm_traffic.json")
+
+WORKLOADS = {
+    # name: (synth config, feature mask or None = the config's, description)
+    "multivariate-20x50k": 2,
+    "univariate-standard": 1,
+    "univariate-tiny": 0,
+    "long-20x200k": 4,
+}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="multivariate-20x50k", choices=sorted(WORKLOADS))
+    ap.add_argument("--batch", type=int, default=None, help="override the workload's batch size")
+    ap.add_argument("--features", type=int, default=None, help="feature mask override (1=max, 2=PPV, 4=softPPV)")
+    ap.add_argument("--lam", type=float, default=10.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-examples", type=int, default=None, help="examples in the oracle's timed sample")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg_id, x_host, kr, mask, lam, n_examples):
+    """Times the oracle (all host threads) on the first n_examples examples x all kernels."""
+    import oracle
+    xs = x_host[:n_examples]
+    t0 = time.perf_counter()
+    oracle.transform(xs, kr, lam=lam, shift=-3.0)
+    dt = time.perf_counter() - t0
+    return {
+        "value": n_examples / dt, "unit": "examples/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "%d example(s) x all %d kernels of the same workload, %.1f s, fp64, all features at once"
+                  % (n_examples, len(kr["length"]), dt),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2301_08527_amd import rocket, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the transform has no CPU path", file=sys.stderr)
+        sys.exit(1)
+
+    cfg_id = WORKLOADS[args.workload]
+    cfg = synth.CONFIGS[cfg_id]
+    B = cfg["B"] if args.batch is None else args.batch
+    mask = cfg["features"] if args.features is None else args.features
+    K, C, L = cfg["K"], cfg["C"], cfg["L"]
+
+    x_host = synth.make_input(cfg_id, B=B)
+    h = rocket.rocket_make_kernels(synth.seed_k(cfg_id), K, C, L)
+    fma_per_series, outputs_per_series = rocket.rocket_work_per_series(h)
+    F = rocket.rocket_num_features(mask)
+
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(x_host).to(dev)
+    out = torch.empty((B, F * K), dtype=torch.float32, device=dev)
+    ws = torch.empty(rocket.rocket_workspace_bytes(h, B, mask), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        rocket.rocket_transform(h, x, mask, args.lam, -3.0, out=out, workspace=ws, stream=stream)
+    torch.cuda.synchronize()
+
+    rocket.rocket_profile_enable(h, True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        rocket.rocket_transform(h, x, mask, args.lam, -3.0, out=out, workspace=ws, stream=stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    launches, kernel_ms = rocket.rocket_profile_read(h)
+    rocket.rocket_profile_enable(h, False)
+    assert launches == args.steps
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = B * args.steps / elapsed
+    kernel_ms_avg = kernel_ms / launches
+    flops_per_launch = 2.0 * fma_per_series * B          # conv FMAs only, as the method defines them
+    achieved = flops_per_launch / (kernel_ms_avg * 1e-3) / 1e12
+    traffic = None
+    if os.path.exists(TRAFFIC_FILE):
+        try:
+            rec = json.load(open(TRAFFIC_FILE))
+            if rec.get("workload") == args.workload and rec.get("batch") == B and rec.get("features") == mask:
+                traffic = rec.get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    line = {
+        "metric": "examples/sec (20ch x 50k, K=10k) and % of FP32 vector peak" if cfg_id == 2 else "series/sec",
+        "value": value, "unit": "examples/s" if cfg_id != 1 and cfg_id != 0 else "series/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "B": B, "C": C, "L": L, "K": K, "features": mask,
+                   "lambda": args.lam, "shift": -3.0, "seed_x": synth.seed_x(cfg_id), "seed_k": synth.seed_k(cfg_id)},
+        "roofline": {
+            "bound": "alu", "achieved": achieved, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": achieved / FP32_VECTOR_PEAK_TFLOPS, "traffic": traffic,
+            "kernel": "rk_forward", "kernel_ms": kernel_ms_avg,
+            "flop_per_launch": flops_per_launch, "fma_per_example": fma_per_series,
+            "pooled_positions_per_example": outputs_per_series,
+            "note": "peak assumes packed FP32; this build uses plain v_fma_f32, whose ceiling is half of it",
+        },
+        "percent_of_fp32_vector_peak": 100.0 * achieved / FP32_VECTOR_PEAK_TFLOPS,
+    }
+
+    if not args.no_cpu_baseline:
+        kr = rocket.rocket_kernels_view_get(h)
+        n_ex = args.cpu_examples
+        if n_ex is None:
+            # aim at 10-30 s of oracle time: the oracle does roughly 0.4 GFMA/s per thread
+            import oracle
+            rate = 0.4e9 * oracle.num_threads()
+            n_ex = int(max(1, min(B, round(15.0 * rate / fma_per_series))))
+        line["cpu_baseline"] = cpu_baseline(cfg_id, x_host, kr, mask, args.lam, n_ex)
+
+    print(json.dumps(line))
+    h.free()
+
+
+if __name__ == "__main__":
+    main()

@@ -153,6 +153,18 @@ int rocket_soft_ppv_backward(rocket_kernels *kernels, const float *x_dev, int32_
  * *outputs receives sum_k n_k (pooled positions per series). */
 int rocket_work_per_series(const rocket_kernels *kernels, double *conv_fma, double *outputs);
 
+/*
+ * Timing of the dominant kernel, for roofline measurement.  While enabled, every
+ * rocket_transform / rocket_soft_ppv_backward call on this handle records a HIP
+ * event pair on its stream around its main kernel (the conv + pooling kernel;
+ * the padding copy and the small reduction kernels are outside the pair).
+ * rocket_profile_read waits for the recorded events, returns the number of
+ * launches and their summed duration in milliseconds since the last read, and
+ * clears the list.  Disabled by default; enabling allocates events per call.
+ */
+int rocket_profile_enable(rocket_kernels *kernels, int enable);
+int rocket_profile_read(rocket_kernels *kernels, int32_t *launches, double *total_ms);
+
 /* Frees a handle and its device mirror; NULL is allowed. */
 void rocket_free_kernels(rocket_kernels *kernels);
 

@@ -207,9 +207,55 @@ extern "C" int rocket_work_per_series(const rocket_kernels *h, double *conv_fma,
     return ROCKET_OK;
 }
 
+static void drop_events(rocket_kernels *h)
+{
+    for (auto &pr : h->events) {
+        (void)hipEventDestroy(static_cast<hipEvent_t>(pr.first));
+        (void)hipEventDestroy(static_cast<hipEvent_t>(pr.second));
+    }
+    h->events.clear();
+}
+
+extern "C" int rocket_profile_enable(rocket_kernels *h, int enable)
+{
+    if (!h) return rk_fail(ROCKET_EINVAL, "rocket_profile_enable: NULL handle");
+    h->profile = enable != 0;
+    if (!h->profile) drop_events(h);
+    return ROCKET_OK;
+}
+
+extern "C" int rocket_profile_read(rocket_kernels *h, int32_t *launches, double *total_ms)
+{
+    if (!h || !launches || !total_ms) return rk_fail(ROCKET_EINVAL, "rocket_profile_read: NULL argument");
+    double sum = 0.0;
+    for (auto &pr : h->events) {
+        float ms = 0.f;
+        RK_HIP(hipEventSynchronize(static_cast<hipEvent_t>(pr.second)));
+        RK_HIP(hipEventElapsedTime(&ms, static_cast<hipEvent_t>(pr.first), static_cast<hipEvent_t>(pr.second)));
+        sum += ms;
+    }
+    *launches = static_cast<int32_t>(h->events.size());
+    *total_ms = sum;
+    drop_events(h);
+    return ROCKET_OK;
+}
+
+// Records the first / second event of a pair on `stream` when profiling is on.
+static int profile_mark(rocket_kernels *h, hipStream_t stream, bool begin)
+{
+    if (!h->profile) return ROCKET_OK;
+    hipEvent_t ev;
+    RK_HIP(hipEventCreate(&ev));
+    if (begin) h->events.emplace_back(ev, nullptr);
+    else h->events.back().second = ev;
+    RK_HIP(hipEventRecord(ev, stream));
+    return ROCKET_OK;
+}
+
 extern "C" void rocket_free_kernels(rocket_kernels *h)
 {
     if (!h) return;
+    drop_events(h);
     if (h->d_blob) {
         int cur = -1;
         if (hipGetDevice(&cur) == hipSuccess && cur != h->device && hipSetDevice(h->device) == hipSuccess) {
@@ -519,6 +565,8 @@ extern "C" int rocket_transform(rocket_kernels *h, const float *x_dev, int32_t B
     rc = launch_pad(h, x_dev, B, xpad, stream);
     if (rc != ROCKET_OK) return rc;
     const float nl = -lambda * kLog2e, ns = -shift * kLog2e;
+    rc = profile_mark(h, stream, true);
+    if (rc != ROCKET_OK) return rc;
     switch (mask) {
         case 1: launch_forward<1>(h, xpad, B, nl, ns, out_dev, stream); break;
         case 2: launch_forward<2>(h, xpad, B, nl, ns, out_dev, stream); break;
@@ -529,7 +577,7 @@ extern "C" int rocket_transform(rocket_kernels *h, const float *x_dev, int32_t B
         default: launch_forward<7>(h, xpad, B, nl, ns, out_dev, stream); break;
     }
     RK_HIP(hipGetLastError());
-    return ROCKET_OK;
+    return profile_mark(h, stream, false);
 }
 
 extern "C" int rocket_soft_ppv_backward(rocket_kernels *h, const float *x_dev, int32_t B, uint32_t mask,

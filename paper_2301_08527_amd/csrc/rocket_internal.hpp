@@ -2,6 +2,7 @@
 #pragma once
 #include <cstdint>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "rocket.h"
@@ -38,6 +39,10 @@ struct rocket_kernels {
     const int32_t *d_order = nullptr;
     const int32_t *d_channels = nullptr;
     float *d_weights = nullptr;
+
+    // optional event pairs around the dominant kernel of each call
+    bool profile = false;
+    std::vector<std::pair<void *, void *>> events;
 };
 
 void rk_set_error(const std::string &msg);

@@ -20,6 +20,7 @@ EXPORTS = [
     "rocket_make_kernels", "rocket_kernels_import", "rocket_kernels_view_get",
     "rocket_kernels_set_params", "rocket_num_features", "rocket_workspace_bytes",
     "rocket_transform", "rocket_soft_ppv_backward", "rocket_work_per_series",
+    "rocket_profile_enable", "rocket_profile_read",
     "rocket_free_kernels", "rocket_last_error",
 ]
 
@@ -66,6 +67,8 @@ def load_library():
     lib.rocket_transform.argtypes = [vp, vp, i32, u32, f32, f32, vp, vp, C.c_size_t, vp]
     lib.rocket_soft_ppv_backward.argtypes = [vp, vp, i32, u32, vp, f32, f32, C.c_int, vp, vp, vp, C.c_size_t, vp]
     lib.rocket_work_per_series.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.rocket_profile_enable.argtypes = [vp, C.c_int]
+    lib.rocket_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]
     lib.rocket_free_kernels.argtypes = [vp]
     lib.rocket_free_kernels.restype = None
     lib.rocket_last_error.restype = C.c_char_p
@@ -163,6 +166,17 @@ def rocket_work_per_series(kernels):
     fma, outs = C.c_double(), C.c_double()
     _check(load_library().rocket_work_per_series(kernels.handle, C.byref(fma), C.byref(outs)))
     return fma.value, outs.value
+
+
+def rocket_profile_enable(kernels, enable=True):
+    _check(load_library().rocket_profile_enable(kernels.handle, int(bool(enable))))
+
+
+def rocket_profile_read(kernels):
+    """(launches, total milliseconds) of the dominant kernel since the last read."""
+    n, ms = C.c_int32(), C.c_double()
+    _check(load_library().rocket_profile_read(kernels.handle, C.byref(n), C.byref(ms)))
+    return n.value, ms.value
 
 
 def _torch():
