@@ -271,7 +271,8 @@ extern "C" void rocket_free_kernels(rocket_kernels *h)
 // workspace layout: [padded batch: B*C*row_len floats][backward: B*(total_w + 2K) floats]
 static size_t padded_batch_bytes(const rocket_kernels *h, int32_t B)
 {
-    return static_cast<size_t>(round_up(static_cast<int64_t>(B) * h->C * h->row_len * 4, 256));
+    // 8 KB of slack: the LDS staging of the last row may read a few hundred floats past it
+    return static_cast<size_t>(round_up(static_cast<int64_t>(B) * h->C * h->row_len * 4 + 8192, 256));
 }
 
 static size_t backward_partial_floats(const rocket_kernels *h) { return static_cast<size_t>(h->w_off[h->K]) + h->K; }
@@ -368,123 +369,207 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t rk_row_buffer(const char *base
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0, static_cast<int>(bytes), 0x00020000);
 }
 
-// R conv outputs of one strip: acc[i] = y[t0 + i*d].  `xk` points at the padded
-// row of channel 0 shifted by -p, so x[c][t - p] is the float at xk + c*row_bytes + 4t.
+__device__ __forceinline__ float rk_load(__amdgpu_buffer_rsrc_t row, uint32_t lane_bytes, uint32_t uniform_bytes)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(row, static_cast<int>(lane_bytes),
+                                                                          static_cast<int>(uniform_bytes), 0));
+}
+
+// One input value of a strip feeds every output it overlaps: acc[i-j] += w[j]*x_i.
 template <int LEN, int R>
-__device__ __forceinline__ void rk_strip_conv(const char *__restrict__ xk, size_t row_bytes, uint32_t span_bytes,
-                                              uint32_t dbytes, uint32_t voff, int nch,
-                                              const int32_t *__restrict__ chans, const float *__restrict__ wts,
-                                              float bias, float (&acc)[R])
+__device__ __forceinline__ void rk_taps(const float (&w)[LEN], float xv, int i, float (&acc)[R])
 {
 #pragma unroll
-    for (int i = 0; i < R; ++i) acc[i] = bias;
-    for (int c = 0; c < nch; ++c) {
-        const __amdgpu_buffer_rsrc_t row = rk_row_buffer(xk + static_cast<size_t>(chans[c]) * row_bytes, span_bytes);
-        float w[LEN];
-#pragma unroll
-        for (int j = 0; j < LEN; ++j) w[j] = wts[c * LEN + j];
-#pragma unroll
-        for (int i = 0; i < R + LEN - 1; ++i) {
-            const float xv = __builtin_bit_cast(
-                float, __builtin_amdgcn_raw_buffer_load_b32(row, static_cast<int>(voff), static_cast<int>(i * dbytes), 0));
-#pragma unroll
-            for (int j = 0; j < LEN; ++j) {
-                const int o = i - j;
-                if (o >= 0 && o < R) acc[o] = fmaf(w[j], xv, acc[o]);
-            }
-        }
+    for (int j = 0; j < LEN; ++j) {
+        const int o = i - j;
+        if (o >= 0 && o < R) acc[o] = fmaf(w[j], xv, acc[o]);
     }
 }
 
-template <int R, int MASK>
-__device__ __forceinline__ void rk_pool(const float (&acc)[R], float nl, float ns, PoolState &st)
+// Pooling of R finished conv outputs (section 3.2).  `mask` is uniform.
+template <int R>
+__device__ __forceinline__ void rk_pool(const float (&acc)[R], uint32_t mask, float nl, float ns, PoolState &st)
 {
-    if (MASK & ROCKET_F_MAX) {
+    if (mask & ROCKET_F_MAX) {
 #pragma unroll
         for (int i = 0; i < R; ++i) st.vmax = fmaxf(st.vmax, acc[i]);
     }
-    if (MASK & ROCKET_F_PPV) {
+    if (mask & ROCKET_F_PPV) {   // Eq. 1-2: strict y > 0, counted per wavefront in a scalar register
 #pragma unroll
         for (int i = 0; i < R; ++i) st.cnt += __builtin_popcountll(__ballot(acc[i] > 0.f));
     }
-    if (MASK & ROCKET_F_SOFTPPV) {
+    if (mask & ROCKET_F_SOFTPPV) {
 #pragma unroll
         for (int i = 0; i < R; ++i) {
-            // 1/(1+exp(-(lambda*y+shift))) with nl = -lambda*log2(e), ns = -shift*log2(e)
+            // Eq. 3: 1/(1+exp(-(lambda*y+shift))) with nl = -lambda*log2(e), ns = -shift*log2(e)
             const float e = __builtin_amdgcn_exp2f(fmaf(acc[i], nl, ns));
             st.ssum += __builtin_amdgcn_rcpf(1.f + e);
         }
     }
 }
 
-// All strips of `nbands` bands of R rows x `ncols` columns starting at row `row0`.
-template <int LEN, int R, int MASK>
-__device__ __forceinline__ void rk_segment(const char *__restrict__ xk, size_t row_bytes, uint32_t span_bytes, int d, int row0,
-                                           int nbands, int ncols, int nch, const int32_t *__restrict__ chans,
-                                           const float *__restrict__ wts, float bias, float nl, float ns,
-                                           PoolState &st)
+struct KernelCtx {
+    const char *xk;        // padded row of channel 0 of this series, shifted by -p (bytes)
+    size_t row_bytes;      // bytes per padded row
+    uint32_t span_bytes;   // bytes from xk to the end of its row
+    const int32_t *chans;  // this kernel's channel list
+    const float *wts;      // this kernel's weights, channel-major
+    int nch, d;
+    float bias;
+    uint32_t mask;
+    float nl, ns;
+};
+
+// Register path.  All strips of `nbands` bands of R rows x `ncols` columns starting at
+// row `row0`; every lane reads its R+LEN-1 inputs straight from global memory
+// (consecutive lanes read consecutive floats once d >= 64).
+template <int LEN, int R>
+__device__ __forceinline__ void rk_segment(const KernelCtx &k, int row0, int nbands, int ncols, PoolState &st)
 {
     const int nstrips = nbands * ncols;
-    const uint32_t dbytes = static_cast<uint32_t>(d) * 4u;
+    const uint32_t dbytes = static_cast<uint32_t>(k.d) * 4u;
     for (int base = 0; base < nstrips; base += kThreads) {
         const int s = base + static_cast<int>(threadIdx.x);
         if (s < nstrips) {
             const int band = (nbands == 1) ? 0 : s / ncols;
             const int r = s - band * ncols;
-            const uint32_t voff = static_cast<uint32_t>((row0 + band * R) * d + r) * 4u;
+            const uint32_t voff = static_cast<uint32_t>((row0 + band * R) * k.d + r) * 4u;
             float acc[R];
-            rk_strip_conv<LEN, R>(xk, row_bytes, span_bytes, dbytes, voff, nch, chans, wts, bias, acc);
-            rk_pool<R, MASK>(acc, nl, ns, st);
+#pragma unroll
+            for (int i = 0; i < R; ++i) acc[i] = k.bias;
+            for (int c = 0; c < k.nch; ++c) {
+                const __amdgpu_buffer_rsrc_t row =
+                    rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+                float w[LEN];
+#pragma unroll
+                for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
+#pragma unroll
+                for (int i = 0; i < R + LEN - 1; ++i) rk_taps<LEN, R>(w, rk_load(row, voff, i * dbytes), i, acc);
+            }
+            rk_pool<R>(acc, k.mask, k.nl, k.ns, st);
         }
     }
 }
 
-template <int LEN, int MASK>
-__device__ __forceinline__ void rk_forward_body(const RkKernelRec rec, const char *__restrict__ xk, size_t row_bytes, uint32_t span_bytes,
-                                                const int32_t *__restrict__ chans, const float *__restrict__ wts,
-                                                float nl, float ns, PoolState &st)
+// LDS path for small dilations.  With d < 64 the strips of a wavefront start
+// kLdsRows*d floats apart, so direct loads would touch a different cache line per
+// lane group.  Instead the workgroup copies the contiguous input range of a
+// chunk of bands into LDS with coalesced loads and the lanes read their strips
+// from there.  Bands have kLdsRows = 17 rows: an odd row count makes the stride
+// between neighbouring bands odd (times d), which spreads the strided LDS reads
+// over the banks without padding.  D is a template parameter so that the LDS
+// read offsets i*D*4 are immediates.
+constexpr int kLdsRows = 17;
+constexpr int kLdsMaxD = 8;                                       // dilations 1..7 take this path
+constexpr int kLdsStage = 4;                                      // staged words per lane per round
+constexpr int kLdsTileWords = ((kLdsRows * kThreads + 10 * (kLdsMaxD - 1)) / (kThreads * kLdsStage) + 1) * kThreads * kLdsStage;
+
+template <int LEN, int D>
+__device__ __forceinline__ int rk_lds_bands(const KernelCtx &k, int rows, float *tile, PoolState &st)
 {
-    const int d = rec.dil;
-    const int rows = rec.nout / d;            // full rows of d outputs
-    const int tail = rec.nout - rows * d;     // outputs of the partial last row
+    constexpr int R = kLdsRows;
+    const int nb = rows / R;
+    if (nb == 0) return 0;
+    constexpr int G = kThreads / D;                 // bands per chunk
+    const int tid = static_cast<int>(threadIdx.x);
+    const int bl = tid / D;                         // lane's band inside the chunk
+    const int r = tid - bl * D;                     // lane's column
+    const float *mine = tile + bl * R * D + r;
+    for (int band0 = 0; band0 < nb; band0 += G) {
+        const int gb = min(G, nb - band0);
+        const bool active = bl < gb;
+        const int nin = (gb * R + LEN - 1) * D;     // input floats of this chunk
+        const uint32_t chunk_bytes = static_cast<uint32_t>(band0 * R * D) * 4u;
+        float acc[R];
+#pragma unroll
+        for (int i = 0; i < R; ++i) acc[i] = k.bias;
+        for (int c = 0; c < k.nch; ++c) {
+            const __amdgpu_buffer_rsrc_t row =
+                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+            float w[LEN];
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
+            __syncthreads();   // everyone is done reading the previous channel's tile
+            for (int base = 0; base < nin; base += kThreads * kLdsStage) {
+                float v[kLdsStage];
+#pragma unroll
+                for (int u = 0; u < kLdsStage; ++u)
+                    v[u] = rk_load(row, static_cast<uint32_t>(tid + u * kThreads) * 4u,
+                                   chunk_bytes + static_cast<uint32_t>(base) * 4u);
+#pragma unroll
+                for (int u = 0; u < kLdsStage; ++u) tile[base + tid + u * kThreads] = v[u];
+            }
+            __syncthreads();
+            if (active) {
+#pragma unroll
+                for (int i = 0; i < R + LEN - 1; ++i) rk_taps<LEN, R>(w, mine[i * D], i, acc);
+            }
+        }
+        if (active) rk_pool<R>(acc, k.mask, k.nl, k.ns, st);
+    }
+    return nb * R;
+}
+
+template <int LEN>
+__device__ __forceinline__ void rk_forward_body(const KernelCtx &k, int nout, float *tile, PoolState &st)
+{
+    const int d = k.d;
+    const int rows = nout / d;            // full rows of d outputs
+    const int tail = nout - rows * d;     // outputs of the partial last row
     int row0 = 0;
-    const int nb16 = rows >> 4;
-    if (nb16) rk_segment<LEN, 16, MASK>(xk, row_bytes, span_bytes, d, 0, nb16, d, rec.nch, chans, wts, rec.bias, nl, ns, st);
-    row0 = nb16 << 4;
-    if (rows & 8) { rk_segment<LEN, 8, MASK>(xk, row_bytes, span_bytes, d, row0, 1, d, rec.nch, chans, wts, rec.bias, nl, ns, st); row0 += 8; }
-    if (rows & 4) { rk_segment<LEN, 4, MASK>(xk, row_bytes, span_bytes, d, row0, 1, d, rec.nch, chans, wts, rec.bias, nl, ns, st); row0 += 4; }
-    if (rows & 2) { rk_segment<LEN, 2, MASK>(xk, row_bytes, span_bytes, d, row0, 1, d, rec.nch, chans, wts, rec.bias, nl, ns, st); row0 += 2; }
-    if (rows & 1) { rk_segment<LEN, 1, MASK>(xk, row_bytes, span_bytes, d, row0, 1, d, rec.nch, chans, wts, rec.bias, nl, ns, st); row0 += 1; }
-    if (tail) rk_segment<LEN, 1, MASK>(xk, row_bytes, span_bytes, d, row0, 1, tail, rec.nch, chans, wts, rec.bias, nl, ns, st);
+    switch (d) {                          // uniform per workgroup
+        case 1: row0 = rk_lds_bands<LEN, 1>(k, rows, tile, st); break;
+        case 2: row0 = rk_lds_bands<LEN, 2>(k, rows, tile, st); break;
+        case 3: row0 = rk_lds_bands<LEN, 3>(k, rows, tile, st); break;
+        case 4: row0 = rk_lds_bands<LEN, 4>(k, rows, tile, st); break;
+        case 5: row0 = rk_lds_bands<LEN, 5>(k, rows, tile, st); break;
+        case 6: row0 = rk_lds_bands<LEN, 6>(k, rows, tile, st); break;
+        case 7: row0 = rk_lds_bands<LEN, 7>(k, rows, tile, st); break;
+        default: break;
+    }
+    const int left = rows - row0;         // rows for the register path
+    const int nb16 = left >> 4;
+    if (nb16) { rk_segment<LEN, 16>(k, row0, nb16, d, st); row0 += nb16 << 4; }
+    if (left & 8) { rk_segment<LEN, 8>(k, row0, 1, d, st); row0 += 8; }
+    if (left & 4) { rk_segment<LEN, 4>(k, row0, 1, d, st); row0 += 4; }
+    if (left & 2) { rk_segment<LEN, 2>(k, row0, 1, d, st); row0 += 2; }
+    if (left & 1) { rk_segment<LEN, 1>(k, row0, 1, d, st); row0 += 1; }
+    if (tail) rk_segment<LEN, 1>(k, row0, 1, tail, st);
 }
 
 // grid: B*K workgroups; workgroup g handles series g / K and kernel order[g % K].
-template <int MASK>
 __global__ __launch_bounds__(kThreads) void rk_forward(const float *__restrict__ xpad, int row_len, int lead, int C, int K,
                                                        const RkKernelRec *__restrict__ recs,
                                                        const int32_t *__restrict__ order,
                                                        const int32_t *__restrict__ channels,
-                                                       const float *__restrict__ weights, float nl, float ns,
-                                                       float *__restrict__ out)
+                                                       const float *__restrict__ weights, uint32_t mask, float nl,
+                                                       float ns, float *__restrict__ out)
 {
+    __shared__ float tile[kLdsTileWords];
     const int b = blockIdx.x / K;
-    const int k = order[blockIdx.x - b * K];
-    const RkKernelRec rec = recs[k];
-    const size_t row_bytes = static_cast<size_t>(row_len) * 4;
-    const char *xk = reinterpret_cast<const char *>(xpad) + static_cast<size_t>(b) * C * row_bytes +
-                     static_cast<size_t>(lead - rec.pad) * 4;
-    // bytes from the shifted row start to the end of the padded row
-    const uint32_t span_bytes = static_cast<uint32_t>(row_len - (lead - rec.pad)) * 4u;
-    const int32_t *chans = channels + rec.ch_off;
-    const float *wts = weights + rec.w_off;
+    const int kid = order[blockIdx.x - b * K];
+    const RkKernelRec rec = recs[kid];
+    KernelCtx k;
+    k.row_bytes = static_cast<size_t>(row_len) * 4;
+    k.xk = reinterpret_cast<const char *>(xpad) + static_cast<size_t>(b) * C * k.row_bytes +
+           static_cast<size_t>(lead - rec.pad) * 4;
+    k.span_bytes = static_cast<uint32_t>(row_len - (lead - rec.pad)) * 4u;
+    k.chans = channels + rec.ch_off;
+    k.wts = weights + rec.w_off;
+    k.nch = rec.nch;
+    k.d = rec.dil;
+    k.bias = rec.bias;
+    k.mask = mask;
+    k.nl = nl;
+    k.ns = ns;
 
     PoolState st;
     st.vmax = -INFINITY;
     st.ssum = 0.f;
     st.cnt = 0;
-    if (rec.len == 7) rk_forward_body<7, MASK>(rec, xk, row_bytes, span_bytes, chans, wts, nl, ns, st);
-    else if (rec.len == 9) rk_forward_body<9, MASK>(rec, xk, row_bytes, span_bytes, chans, wts, nl, ns, st);
-    else rk_forward_body<11, MASK>(rec, xk, row_bytes, span_bytes, chans, wts, nl, ns, st);
+    if (rec.len == 7) rk_forward_body<7>(k, rec.nout, tile, st);
+    else if (rec.len == 9) rk_forward_body<9>(k, rec.nout, tile, st);
+    else rk_forward_body<11>(k, rec.nout, tile, st);
 
     // close the reductions: lanes -> wavefront (shuffles) -> workgroup (LDS)
     float vmax = st.vmax, ssum = st.ssum;
@@ -504,12 +589,12 @@ __global__ __launch_bounds__(kThreads) void rk_forward(const float *__restrict__
         int cn = s_cnt[0];
 #pragma unroll
         for (int w = 1; w < kWaves; ++w) { m = fmaxf(m, s_max[w]); sm += s_sum[w]; cn += s_cnt[w]; }
-        constexpr int F = ((MASK & 1) ? 1 : 0) + ((MASK & 2) ? 1 : 0) + ((MASK & 4) ? 1 : 0);
-        float *o = out + static_cast<size_t>(b) * F * K + k;
+        const int F = __builtin_popcount(mask);
+        float *o = out + static_cast<size_t>(b) * F * K + kid;
         int f = 0;
-        if (MASK & ROCKET_F_MAX) { o[static_cast<size_t>(f) * K] = m; ++f; }
-        if (MASK & ROCKET_F_PPV) { o[static_cast<size_t>(f) * K] = static_cast<float>(static_cast<double>(cn) / static_cast<double>(rec.nout)); ++f; }
-        if (MASK & ROCKET_F_SOFTPPV) { o[static_cast<size_t>(f) * K] = sm / static_cast<float>(rec.nout); ++f; }
+        if (mask & ROCKET_F_MAX) { o[static_cast<size_t>(f) * K] = m; ++f; }
+        if (mask & ROCKET_F_PPV) { o[static_cast<size_t>(f) * K] = static_cast<float>(static_cast<double>(cn) / static_cast<double>(rec.nout)); ++f; }
+        if (mask & ROCKET_F_SOFTPPV) { o[static_cast<size_t>(f) * K] = sm / static_cast<float>(rec.nout); ++f; }
     }
 }
 
@@ -542,15 +627,6 @@ static int launch_pad(const rocket_kernels *h, const float *x, int32_t B, float 
     return ROCKET_OK;
 }
 
-template <int MASK>
-static void launch_forward(const rocket_kernels *h, const float *xpad, int32_t B, float nl, float ns, float *out,
-                           hipStream_t stream)
-{
-    hipLaunchKernelGGL(rk_forward<MASK>, dim3(static_cast<unsigned>(B) * h->K), dim3(kThreads), 0, stream, xpad,
-                       static_cast<int>(h->row_len), h->lead, h->C, h->K, h->d_rec, h->d_order, h->d_channels,
-                       h->d_weights, nl, ns, out);
-}
-
 extern "C" int rocket_transform(rocket_kernels *h, const float *x_dev, int32_t B, uint32_t mask, float lambda,
                                 float shift, float *out_dev, void *ws, size_t ws_bytes, void *hip_stream)
 {
@@ -567,15 +643,9 @@ extern "C" int rocket_transform(rocket_kernels *h, const float *x_dev, int32_t B
     const float nl = -lambda * kLog2e, ns = -shift * kLog2e;
     rc = profile_mark(h, stream, true);
     if (rc != ROCKET_OK) return rc;
-    switch (mask) {
-        case 1: launch_forward<1>(h, xpad, B, nl, ns, out_dev, stream); break;
-        case 2: launch_forward<2>(h, xpad, B, nl, ns, out_dev, stream); break;
-        case 3: launch_forward<3>(h, xpad, B, nl, ns, out_dev, stream); break;
-        case 4: launch_forward<4>(h, xpad, B, nl, ns, out_dev, stream); break;
-        case 5: launch_forward<5>(h, xpad, B, nl, ns, out_dev, stream); break;
-        case 6: launch_forward<6>(h, xpad, B, nl, ns, out_dev, stream); break;
-        default: launch_forward<7>(h, xpad, B, nl, ns, out_dev, stream); break;
-    }
+    hipLaunchKernelGGL(rk_forward, dim3(static_cast<unsigned>(B) * h->K), dim3(kThreads), 0, stream, xpad,
+                       static_cast<int>(h->row_len), h->lead, h->C, h->K, h->d_rec, h->d_order, h->d_channels,
+                       h->d_weights, mask, nl, ns, out_dev);
     RK_HIP(hipGetLastError());
     return profile_mark(h, stream, false);
 }
