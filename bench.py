@@ -23,6 +23,7 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "rk_forward_hbm_traffic.json")
 WORKLOADS = {
     # name: (synth config, feature mask or None = the config's, description)
     "multivariate-20x50k": 2,
+    "multivariate-20x50k-grad": 3,
     "univariate-standard": 1,
     "univariate-tiny": 0,
     "long-20x200k": 4,
@@ -89,16 +90,40 @@ def main():
     ws = torch.empty(rocket.rocket_workspace_bytes(h, B, mask), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
-    for _ in range(args.warmup):
+    with_grad = cfg_id == 3
+    if with_grad:
+        # forward (max + softPPV), then the backward pass from a seeded N(0,1) upstream gradient
+        view = rocket.rocket_kernels_view_get(h)
+        gout = torch.from_numpy(synth.make_upstream_grad(cfg_id, B, F * K)).to(dev)
+        gw = torch.empty(len(view["weights"]), dtype=torch.float32, device=dev)
+        gb = torch.empty(K, dtype=torch.float32, device=dev)
+        ws = torch.empty(rocket.rocket_workspace_bytes(h, B, mask, True), dtype=torch.uint8, device=dev)
+
+    def backward():
+        rocket.rocket_soft_ppv_backward(h, x, mask, gout, args.lam, -3.0, True, grad_w=gw, grad_b=gb,
+                                        workspace=ws, stream=stream)
+
+    def step():
         rocket.rocket_transform(h, x, mask, args.lam, -3.0, out=out, workspace=ws, stream=stream)
+        if with_grad:
+            backward()
+
+    for _ in range(args.warmup):
+        step()
     torch.cuda.synchronize()
 
-    rocket.rocket_profile_enable(h, True)
+    rocket.rocket_profile_enable(h, not with_grad)
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        rocket.rocket_transform(h, x, mask, args.lam, -3.0, out=out, workspace=ws, stream=stream)
+        step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    if with_grad:
+        # the dominant kernel of this workload is the backward one: time it alone, after the timed region
+        rocket.rocket_profile_enable(h, True)
+        for _ in range(args.steps):
+            backward()
+        torch.cuda.synchronize()
     launches, kernel_ms = rocket.rocket_profile_read(h)
     rocket.rocket_profile_enable(h, False)
     assert launches == args.steps
@@ -106,7 +131,9 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     value = B * args.steps / elapsed
     kernel_ms_avg = kernel_ms / launches
-    flops_per_launch = 2.0 * fma_per_series * B          # conv FMAs only, as the method defines them
+    # conv FMAs only, as the method defines them; the backward kernel recomputes the conv
+    # and does as many multiply-adds again for the weight gradient
+    flops_per_launch = 2.0 * fma_per_series * B * (2.0 if with_grad else 1.0)
     achieved = flops_per_launch / (kernel_ms_avg * 1e-3) / 1e12
     traffic = None
     if os.path.exists(TRAFFIC_FILE):
@@ -118,7 +145,9 @@ def main():
             traffic = None
 
     line = {
-        "metric": "examples/sec (20ch x 50k, K=10k) and % of FP32 vector peak" if cfg_id == 2 else "series/sec",
+        "metric": ("examples/sec (20ch x 50k, K=10k) and % of FP32 vector peak" if cfg_id == 2 else
+                   "examples/sec, forward + softPPV backward (20ch x 50k, K=10k)" if cfg_id == 3 else
+                   "series/sec" if cfg_id in (0, 1) else "examples/sec"),
         "value": value, "unit": "examples/s" if cfg_id != 1 and cfg_id != 0 else "series/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -128,7 +157,7 @@ def main():
         "roofline": {
             "bound": "alu", "achieved": achieved, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": achieved / FP32_VECTOR_PEAK_TFLOPS, "traffic": traffic,
-            "kernel": "rk_forward", "kernel_ms": kernel_ms_avg,
+            "kernel": "rk_backward" if with_grad else "rk_forward", "kernel_ms": kernel_ms_avg,
             "flop_per_launch": flops_per_launch, "fma_per_example": fma_per_series,
             "pooled_positions_per_example": outputs_per_series,
             "note": "peak assumes packed FP32; this build uses plain v_fma_f32, whose ceiling is half of it",
@@ -136,7 +165,7 @@ def main():
         "percent_of_fp32_vector_peak": 100.0 * achieved / FP32_VECTOR_PEAK_TFLOPS,
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not with_grad:
         kr = rocket.rocket_kernels_view_get(h)
         n_ex = args.cpu_examples
         if n_ex is None:

@@ -142,6 +142,9 @@ int rocket_transform(rocket_kernels *kernels, const float *x_dev, int32_t B, uin
  * zero gradient and is ignored.  grad_w_dev: device, total_weights floats in
  * the layout of `weights`; grad_b_dev: device, K floats.  No gradient with
  * respect to x.  workspace: rocket_workspace_bytes(kernels, B, mask, 1) bytes.
+ * Kernels with more than 9 channels (possible only through rocket_kernels_import)
+ * are rejected with ROCKET_ESHAPE.  Sums over positions use LDS atomic adds, so two
+ * runs agree up to fp32 rounding order; the sum over the batch is in a fixed order.
  */
 int rocket_soft_ppv_backward(rocket_kernels *kernels, const float *x_dev, int32_t B, uint32_t feature_mask,
                              const float *grad_out_dev, float lambda, float shift, int include_max,

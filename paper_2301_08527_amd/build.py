@@ -19,6 +19,28 @@ def sources():
            [os.path.join(ROOT, "include", "rocket.h")]
 
 
+# Instructions that must not appear in the kernels: indirect register-file indexing
+# (an accumulator array indexed at run time) and scratch (spilled) memory traffic.
+FORBIDDEN = ("s_set_gpr_idx_on", "v_movrel", "scratch_load", "scratch_store")
+
+
+def check_device_code(verbose=False):
+    """Emits the gfx950 assembly of the kernels and fails if it holds a forbidden instruction."""
+    asm = os.path.join(CSRC, "rocket.gfx950.s")
+    cmd = [HIPCC] + DEVICE + COMMON + ["--cuda-device-only", "-S", os.path.join(CSRC, "rocket.hip"), "-o", asm]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.check_call(cmd)
+    text = open(asm).read()
+    os.remove(asm)
+    bad = [w for w in FORBIDDEN if w in text]
+    if bad:
+        raise RuntimeError("device code contains %s: a register array is indexed at run time or spilled" % bad)
+    for line in text.splitlines():
+        if ".private_segment_fixed_size:" in line and line.split(":")[1].strip() != "0":
+            raise RuntimeError("a kernel uses scratch memory: " + line.strip())
+
+
 def build(force=True, verbose=False):
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(s) for s in sources()):
         return LIB
@@ -35,6 +57,7 @@ def build(force=True, verbose=False):
             print(" ".join(full))
         subprocess.check_call(full)
         objs.append(obj)
+    check_device_code(verbose)
     link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     if verbose:
         print(" ".join(link))

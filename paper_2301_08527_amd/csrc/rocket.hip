@@ -23,6 +23,7 @@
 #include <cmath>
 #include <cstring>
 #include <new>
+#include <type_traits>
 
 #include "rocket_internal.hpp"
 
@@ -57,6 +58,7 @@ int rk_finish_handle(rocket_kernels &h)
     h.pad_max = 0;
     h.conv_fma = 0.0;
     h.outputs = 0.0;
+    h.max_terms = 0;
     std::vector<double> cost(K);
     for (int32_t k = 0; k < K; ++k) {
         h.ch_off[k + 1] = h.ch_off[k] + h.n_ch[k];
@@ -65,6 +67,7 @@ int rk_finish_handle(rocket_kernels &h)
                           static_cast<int64_t>(h.length[k] - 1) * h.dilation[k];
         if (n < 1) return rk_fail(ROCKET_ESHAPE, "kernel " + std::to_string(k) + " has no output position");
         h.pad_max = std::max(h.pad_max, h.padding[k]);
+        h.max_terms = std::max(h.max_terms, h.n_ch[k] * h.length[k]);
         cost[k] = static_cast<double>(n) * h.n_ch[k] * h.length[k];
         h.conv_fma += cost[k];
         h.outputs += static_cast<double>(n);
@@ -332,6 +335,12 @@ static int ensure_device(rocket_kernels *h, hipStream_t stream)
 
 // ------------------------------------------------------------------ kernels
 
+#ifndef RK_RMAX
+#define RK_RMAX 32
+#endif
+#ifndef RK_WPE
+#define RK_WPE 6
+#endif
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr float kLog2e = 1.4426950408889634f;
@@ -375,20 +384,37 @@ __device__ __forceinline__ float rk_load(__amdgpu_buffer_rsrc_t row, uint32_t la
                                                                           static_cast<int>(uniform_bytes), 0));
 }
 
-// One input value of a strip feeds every output it overlaps: acc[i-j] += w[j]*x_i.
-template <int LEN, int R>
-__device__ __forceinline__ void rk_taps(const float (&w)[LEN], float xv, int i, float (&acc)[R])
+// Compile-time loop: f(integral_constant<int, I>) for I in [I0, N).  Every index into
+// the per-lane accumulator and weight arrays below comes from such a constant, so the
+// arrays always live in named registers (a run-time index would make the compiler
+// address the register file indirectly).
+template <int I0, int N, class F>
+__device__ __forceinline__ void rk_static_for(F &&f)
 {
-#pragma unroll
-    for (int j = 0; j < LEN; ++j) {
-        const int o = i - j;
-        if (o >= 0 && o < R) acc[o] = fmaf(w[j], xv, acc[o]);
+    if constexpr (I0 < N) {
+        f(std::integral_constant<int, I0>{});
+        rk_static_for<I0 + 1, N>(f);
     }
 }
 
-// Pooling of R finished conv outputs (section 3.2).  `mask` is uniform.
+// Input value number I of a strip feeds every output it overlaps: acc[I-j] += w[j]*x_I.
+template <int LEN, int R, int I>
+__device__ __forceinline__ void rk_taps(const float (&w)[LEN], float xv, float (&acc)[R])
+{
+    rk_static_for<0, LEN>([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        constexpr int o = I - j;
+        if constexpr (o >= 0 && o < R) acc[o] = fmaf(w[j], xv, acc[o]);
+    });
+}
+
+// Pooling of R finished sums z = y - bias (section 3.2).  The bias is folded into
+// the pooling: max(y) = max(z) + bias (added once per kernel at the end),
+// y > 0 <=> z > -bias, and lambda*y + shift = lambda*z + (shift + lambda*bias).
+// `mask` is uniform; ns already contains the bias term.
 template <int R>
-__device__ __forceinline__ void rk_pool(const float (&acc)[R], uint32_t mask, float nl, float ns, PoolState &st)
+__device__ __forceinline__ void rk_pool(const float (&acc)[R], uint32_t mask, float negbias, float nl, float ns,
+                                        PoolState &st)
 {
     if (mask & ROCKET_F_MAX) {
 #pragma unroll
@@ -396,12 +422,12 @@ __device__ __forceinline__ void rk_pool(const float (&acc)[R], uint32_t mask, fl
     }
     if (mask & ROCKET_F_PPV) {   // Eq. 1-2: strict y > 0, counted per wavefront in a scalar register
 #pragma unroll
-        for (int i = 0; i < R; ++i) st.cnt += __builtin_popcountll(__ballot(acc[i] > 0.f));
+        for (int i = 0; i < R; ++i) st.cnt += __builtin_popcountll(__ballot(acc[i] > negbias));
     }
     if (mask & ROCKET_F_SOFTPPV) {
 #pragma unroll
         for (int i = 0; i < R; ++i) {
-            // Eq. 3: 1/(1+exp(-(lambda*y+shift))) with nl = -lambda*log2(e), ns = -shift*log2(e)
+            // Eq. 3: 1/(1+exp(-(lambda*y+shift))) with nl = -lambda*log2(e), ns = -(shift+lambda*bias)*log2(e)
             const float e = __builtin_amdgcn_exp2f(fmaf(acc[i], nl, ns));
             st.ssum += __builtin_amdgcn_rcpf(1.f + e);
         }
@@ -415,9 +441,9 @@ struct KernelCtx {
     const int32_t *chans;  // this kernel's channel list
     const float *wts;      // this kernel's weights, channel-major
     int nch, d;
-    float bias;
+    float negbias;         // -bias
     uint32_t mask;
-    float nl, ns;
+    float nl, ns;          // softPPV: exp2(z*nl + ns) = exp(-(lambda*y + shift))
 };
 
 // Register path.  All strips of `nbands` bands of R rows x `ncols` columns starting at
@@ -435,18 +461,21 @@ __device__ __forceinline__ void rk_segment(const KernelCtx &k, int row0, int nba
             const int r = s - band * ncols;
             const uint32_t voff = static_cast<uint32_t>((row0 + band * R) * k.d + r) * 4u;
             float acc[R];
-#pragma unroll
-            for (int i = 0; i < R; ++i) acc[i] = k.bias;
-            for (int c = 0; c < k.nch; ++c) {
+            auto channel = [&](int c) {
                 const __amdgpu_buffer_rsrc_t row =
                     rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
                 float w[LEN];
 #pragma unroll
                 for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
+                rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    rk_taps<LEN, R, i>(w, rk_load(row, voff, i * dbytes), acc);
+                });
+            };
 #pragma unroll
-                for (int i = 0; i < R + LEN - 1; ++i) rk_taps<LEN, R>(w, rk_load(row, voff, i * dbytes), i, acc);
-            }
-            rk_pool<R>(acc, k.mask, k.nl, k.ns, st);
+            for (int i = 0; i < R; ++i) acc[i] = 0.f;
+            for (int c = 0; c < k.nch; ++c) channel(c);
+            rk_pool<R>(acc, k.mask, k.negbias, k.nl, k.ns, st);
         }
     }
 }
@@ -481,9 +510,7 @@ __device__ __forceinline__ int rk_lds_bands(const KernelCtx &k, int rows, float 
         const int nin = (gb * R + LEN - 1) * D;     // input floats of this chunk
         const uint32_t chunk_bytes = static_cast<uint32_t>(band0 * R * D) * 4u;
         float acc[R];
-#pragma unroll
-        for (int i = 0; i < R; ++i) acc[i] = k.bias;
-        for (int c = 0; c < k.nch; ++c) {
+        auto channel = [&](int c) {
             const __amdgpu_buffer_rsrc_t row =
                 rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
             float w[LEN];
@@ -501,11 +528,16 @@ __device__ __forceinline__ int rk_lds_bands(const KernelCtx &k, int rows, float 
             }
             __syncthreads();
             if (active) {
-#pragma unroll
-                for (int i = 0; i < R + LEN - 1; ++i) rk_taps<LEN, R>(w, mine[i * D], i, acc);
+                rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    rk_taps<LEN, R, i>(w, mine[i * D], acc);
+                });
             }
-        }
-        if (active) rk_pool<R>(acc, k.mask, k.nl, k.ns, st);
+        };
+#pragma unroll
+        for (int i = 0; i < R; ++i) acc[i] = 0.f;
+        for (int c = 0; c < k.nch; ++c) channel(c);
+        if (active) rk_pool<R>(acc, k.mask, k.negbias, k.nl, k.ns, st);
     }
     return nb * R;
 }
@@ -528,8 +560,14 @@ __device__ __forceinline__ void rk_forward_body(const KernelCtx &k, int nout, fl
         default: break;
     }
     const int left = rows - row0;         // rows for the register path
+#if RK_RMAX == 32
+    const int nb32 = left >> 5;
+    if (nb32) { rk_segment<LEN, 32>(k, row0, nb32, d, st); row0 += nb32 << 5; }
+    if (left & 16) { rk_segment<LEN, 16>(k, row0, 1, d, st); row0 += 16; }
+#else
     const int nb16 = left >> 4;
     if (nb16) { rk_segment<LEN, 16>(k, row0, nb16, d, st); row0 += nb16 << 4; }
+#endif
     if (left & 8) { rk_segment<LEN, 8>(k, row0, 1, d, st); row0 += 8; }
     if (left & 4) { rk_segment<LEN, 4>(k, row0, 1, d, st); row0 += 4; }
     if (left & 2) { rk_segment<LEN, 2>(k, row0, 1, d, st); row0 += 2; }
@@ -538,6 +576,9 @@ __device__ __forceinline__ void rk_forward_body(const KernelCtx &k, int nout, fl
 }
 
 // grid: B*K workgroups; workgroup g handles series g / K and kernel order[g % K].
+#if RK_WPE
+__attribute__((amdgpu_waves_per_eu(RK_WPE)))
+#endif
 __global__ __launch_bounds__(kThreads) void rk_forward(const float *__restrict__ xpad, int row_len, int lead, int C, int K,
                                                        const RkKernelRec *__restrict__ recs,
                                                        const int32_t *__restrict__ order,
@@ -558,10 +599,10 @@ __global__ __launch_bounds__(kThreads) void rk_forward(const float *__restrict__
     k.wts = weights + rec.w_off;
     k.nch = rec.nch;
     k.d = rec.dil;
-    k.bias = rec.bias;
+    k.negbias = -rec.bias;
     k.mask = mask;
     k.nl = nl;
-    k.ns = ns;
+    k.ns = fmaf(rec.bias, nl, ns);
 
     PoolState st;
     st.vmax = -INFINITY;
@@ -592,10 +633,225 @@ __global__ __launch_bounds__(kThreads) void rk_forward(const float *__restrict__
         const int F = __builtin_popcount(mask);
         float *o = out + static_cast<size_t>(b) * F * K + kid;
         int f = 0;
-        if (mask & ROCKET_F_MAX) { o[static_cast<size_t>(f) * K] = m; ++f; }
+        if (mask & ROCKET_F_MAX) { o[static_cast<size_t>(f) * K] = m + rec.bias; ++f; }
         if (mask & ROCKET_F_PPV) { o[static_cast<size_t>(f) * K] = static_cast<float>(static_cast<double>(cn) / static_cast<double>(rec.nout)); ++f; }
         if (mask & ROCKET_F_SOFTPPV) { o[static_cast<size_t>(f) * K] = sm / static_cast<float>(rec.nout); ++f; }
     }
+}
+
+// ------------------------------------------------------------------ backward kernels
+//
+// Backward pass through softPPV (and, optionally, the max): one workgroup per
+// (series, kernel), the same strip decomposition as the forward pass.  Per strip:
+//   1. recompute the R conv outputs,
+//   2. turn them into q_i = g_soft * (lambda/n) * s_i (1 - s_i),
+//   3. per channel, re-read the strip's inputs and form the lane's share of
+//      d/dw[c][j] = sum_i q_i * x[c][t_i + j*d - p]  (R*LEN multiply-adds),
+//      then add it to a per-lane-slot accumulator in LDS (slot = lane index in
+//      its wavefront, so the four wavefronts of a workgroup share slots and use
+//      LDS atomic adds, which never collide inside one instruction).
+// At the end the slots are summed and the workgroup writes its partial gradient
+// row partial[b][...]; a second kernel sums the rows over the batch in a fixed
+// order, so the result does not depend on scheduling across workgroups.
+
+constexpr int kBwdMaxTerms = 9 * 11;     // n_ch <= 9 channels x len <= 11 weights
+
+struct BwdState {
+    float qsum;     // per lane: sum of q (bias gradient)
+    float vmax;     // per lane: running max of z = y - bias
+    int targ;       // per lane: first position attaining vmax
+};
+
+// softPPV derivative factor: given z = y - bias returns s(1-s) with
+// s = 1/(1+e), e = exp(-(lambda*y+shift)) = exp2(z*nl + ns).  The exponent is capped so
+// that e stays finite; 1-s is formed as e*s, which keeps its relative accuracy
+// when s is close to 1.
+__device__ __forceinline__ float rk_dsigmoid(float z, float nl, float ns)
+{
+    const float e = __builtin_amdgcn_exp2f(fminf(fmaf(z, nl, ns), 80.f));
+    const float sg = __builtin_amdgcn_rcpf(1.f + e);
+    return sg * (e * sg);
+}
+
+template <int LEN, int R>
+__device__ __forceinline__ void rk_bwd_segment(const KernelCtx &k, int row0, int nbands, int ncols, float coef,
+                                               bool want_max, float *slots, BwdState &st)
+{
+    const int nstrips = nbands * ncols;
+    const uint32_t dbytes = static_cast<uint32_t>(k.d) * 4u;
+    const int lane = static_cast<int>(threadIdx.x) & 63;
+    for (int base = 0; base < nstrips; base += kThreads) {
+        const int s = base + static_cast<int>(threadIdx.x);
+        if (s < nstrips) {
+            const int band = (nbands == 1) ? 0 : s / ncols;
+            const int r = s - band * ncols;
+            const int t0 = (row0 + band * R) * k.d + r;
+            const uint32_t voff = static_cast<uint32_t>(t0) * 4u;
+            float acc[R];
+#pragma unroll
+            for (int i = 0; i < R; ++i) acc[i] = 0.f;
+            for (int c = 0; c < k.nch; ++c) {
+                const __amdgpu_buffer_rsrc_t row =
+                    rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+                float w[LEN];
+#pragma unroll
+                for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
+                rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    rk_taps<LEN, R, i>(w, rk_load(row, voff, i * dbytes), acc);
+                });
+            }
+            if (want_max) {
+#pragma unroll
+                for (int i = 0; i < R; ++i) {
+                    if (acc[i] > st.vmax) { st.vmax = acc[i]; st.targ = t0 + i * k.d; }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+                acc[i] = coef * rk_dsigmoid(acc[i], k.nl, k.ns);   // acc now holds q
+                st.qsum += acc[i];
+            }
+            for (int c = 0; c < k.nch; ++c) {
+                const __amdgpu_buffer_rsrc_t row =
+                    rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+                float g[LEN];
+#pragma unroll
+                for (int j = 0; j < LEN; ++j) g[j] = 0.f;
+                rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    const float xv = rk_load(row, voff, i * dbytes);
+                    rk_static_for<0, LEN>([&](auto jc) {
+                        constexpr int j = decltype(jc)::value;
+                        constexpr int o = i - j;
+                        if constexpr (o >= 0 && o < R) g[j] = fmaf(acc[o], xv, g[j]);
+                    });
+                });
+                float *slot = slots + (c * LEN) * 64 + lane;
+#pragma unroll
+                for (int j = 0; j < LEN; ++j) atomicAdd(slot + j * 64, g[j]);
+            }
+        }
+    }
+}
+
+template <int LEN>
+__device__ __forceinline__ void rk_backward_body(const KernelCtx &k, int nout, float coef, bool want_max,
+                                                 float *slots, BwdState &st)
+{
+    const int d = k.d;
+    const int rows = nout / d;
+    const int tail = nout - rows * d;
+    int row0 = 0;
+    const int nb16 = rows >> 4;
+    if (nb16) { rk_bwd_segment<LEN, 16>(k, row0, nb16, d, coef, want_max, slots, st); row0 += nb16 << 4; }
+    if (rows & 8) { rk_bwd_segment<LEN, 8>(k, row0, 1, d, coef, want_max, slots, st); row0 += 8; }
+    if (rows & 4) { rk_bwd_segment<LEN, 4>(k, row0, 1, d, coef, want_max, slots, st); row0 += 4; }
+    if (rows & 2) { rk_bwd_segment<LEN, 2>(k, row0, 1, d, coef, want_max, slots, st); row0 += 2; }
+    if (rows & 1) { rk_bwd_segment<LEN, 1>(k, row0, 1, d, coef, want_max, slots, st); row0 += 1; }
+    if (tail) rk_bwd_segment<LEN, 1>(k, row0, 1, tail, coef, want_max, slots, st);
+}
+
+// grid: B*K workgroups.  grad_out is B x (F*K); plane_soft / plane_max are the plane
+// indices of the softPPV and max features in it (plane_max < 0: max not included).
+// partial is B rows of (total_w + K) floats: weight gradients in the layout of
+// `weights`, then the K bias gradients.
+__global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict__ xpad, int row_len, int lead, int C, int K,
+                                                        const RkKernelRec *__restrict__ recs,
+                                                        const int32_t *__restrict__ order,
+                                                        const int32_t *__restrict__ channels,
+                                                        const float *__restrict__ weights,
+                                                        const float *__restrict__ grad_out, int F, int plane_soft,
+                                                        int plane_max, float lambda, float nl, float ns,
+                                                        float *__restrict__ partial, int total_w)
+{
+    __shared__ float slots[kBwdMaxTerms * 64];
+    __shared__ float s_q[kWaves];
+    __shared__ float s_max[kWaves];
+    __shared__ int s_arg[kWaves];
+    const int b = blockIdx.x / K;
+    const int kid = order[blockIdx.x - b * K];
+    const RkKernelRec rec = recs[kid];
+    KernelCtx k;
+    k.row_bytes = static_cast<size_t>(row_len) * 4;
+    k.xk = reinterpret_cast<const char *>(xpad) + static_cast<size_t>(b) * C * k.row_bytes +
+           static_cast<size_t>(lead - rec.pad) * 4;
+    k.span_bytes = static_cast<uint32_t>(row_len - (lead - rec.pad)) * 4u;
+    k.chans = channels + rec.ch_off;
+    k.wts = weights + rec.w_off;
+    k.nch = rec.nch;
+    k.d = rec.dil;
+    k.negbias = -rec.bias;
+    k.mask = 0;
+    k.nl = nl;
+    k.ns = fmaf(rec.bias, nl, ns);
+
+    const int nterms = rec.nch * rec.len;
+    for (int i = threadIdx.x; i < nterms * 64; i += kThreads) slots[i] = 0.f;
+    __syncthreads();
+
+    const float *g_row = grad_out + static_cast<size_t>(b) * F * K;
+    const float g_soft = g_row[static_cast<size_t>(plane_soft) * K + kid];
+    const float coef = g_soft * lambda / static_cast<float>(rec.nout);
+    const bool want_max = plane_max >= 0;
+
+    BwdState st;
+    st.qsum = 0.f;
+    st.vmax = -INFINITY;
+    st.targ = 0;
+    if (rec.len == 7) rk_backward_body<7>(k, rec.nout, coef, want_max, slots, st);
+    else if (rec.len == 9) rk_backward_body<9>(k, rec.nout, coef, want_max, slots, st);
+    else rk_backward_body<11>(k, rec.nout, coef, want_max, slots, st);
+
+    // close the lane reductions: sum of q, and (max, first position) pairs
+    float qsum = st.qsum, vmax = st.vmax;
+    int targ = st.targ;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        qsum += __shfl_xor(qsum, off);
+        const float om = __shfl_xor(vmax, off);
+        const int ot = __shfl_xor(targ, off);
+        if (om > vmax || (om == vmax && ot < targ)) { vmax = om; targ = ot; }
+    }
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { s_q[wave] = qsum; s_max[wave] = vmax; s_arg[wave] = targ; }
+    __syncthreads();   // also orders the LDS atomics before the slot sums below
+    float gq = s_q[0], gm = s_max[0];
+    int ga = s_arg[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) {
+        gq += s_q[w];
+        if (s_max[w] > gm || (s_max[w] == gm && s_arg[w] < ga)) { gm = s_max[w]; ga = s_arg[w]; }
+    }
+    const float g_max = want_max ? g_row[static_cast<size_t>(plane_max) * K + kid] : 0.f;
+
+    float *prow = partial + static_cast<size_t>(b) * (static_cast<size_t>(total_w) + K);
+    const int t = static_cast<int>(threadIdx.x);
+    if (t < nterms) {
+        // rotate the start so that the threads of a wavefront hit different banks
+        float sum = 0.f;
+        for (int l = 0; l < 64; ++l) sum += slots[t * 64 + ((l + t) & 63)];
+        if (want_max) {
+            const int c = t / rec.len, j = t - c * rec.len;
+            const float *xrow = reinterpret_cast<const float *>(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes);
+            sum = fmaf(g_max, xrow[ga + j * rec.dil], sum);
+        }
+        prow[rec.w_off + t] = sum;
+    }
+    if (t == 0) prow[total_w + kid] = gq + g_max;
+}
+
+// out[i] = sum_b partial[b][i] for i < width, in ascending b; the first total_w
+// entries go to grad_w, the remaining K to grad_b.
+__global__ __launch_bounds__(256) void rk_reduce_batch(const float *__restrict__ partial, int B, int width, int total_w,
+                                                       float *__restrict__ grad_w, float *__restrict__ grad_b)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= width) return;
+    float sum = 0.f;
+    for (int b = 0; b < B; ++b) sum += partial[static_cast<size_t>(b) * width + i];
+    if (i < total_w) grad_w[i] = sum;
+    else grad_b[i - total_w] = sum;
 }
 
 // ------------------------------------------------------------------ launches
@@ -660,6 +916,32 @@ extern "C" int rocket_soft_ppv_backward(rocket_kernels *h, const float *x_dev, i
     if (!(mask & ROCKET_F_SOFTPPV)) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: mask must contain ROCKET_F_SOFTPPV");
     if (include_max && !(mask & ROCKET_F_MAX)) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: include_max needs ROCKET_F_MAX in the mask");
     if (!grad_out_dev || !grad_w_dev || !grad_b_dev) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: NULL gradient pointer");
-    (void)hip_stream;
-    return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: not built yet");
+    if (h->row_len > INT32_MAX) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: series too long");
+    if (h->max_terms > kBwdMaxTerms)
+        return rk_fail(ROCKET_ESHAPE, "rocket_soft_ppv_backward: a kernel has more than 9 channels x 11 weights");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    rc = ensure_device(h, stream);
+    if (rc != ROCKET_OK) return rc;
+    float *xpad = static_cast<float *>(ws);
+    float *partial = reinterpret_cast<float *>(static_cast<char *>(ws) + padded_batch_bytes(h, B));
+    rc = launch_pad(h, x_dev, B, xpad, stream);
+    if (rc != ROCKET_OK) return rc;
+    const int F = rocket_num_features(mask);
+    const int plane_soft = F - 1;                 // planes are in bit order: softPPV is last
+    const int plane_max = include_max ? 0 : -1;   // and max, when present, is first
+    const float nl = -lambda * kLog2e, ns = -shift * kLog2e;
+    const int total_w = static_cast<int>(h->w_off[h->K]);
+    rc = profile_mark(h, stream, true);
+    if (rc != ROCKET_OK) return rc;
+    hipLaunchKernelGGL(rk_backward, dim3(static_cast<unsigned>(B) * h->K), dim3(kThreads), 0, stream, xpad,
+                       static_cast<int>(h->row_len), h->lead, h->C, h->K, h->d_rec, h->d_order, h->d_channels,
+                       h->d_weights, grad_out_dev, F, plane_soft, plane_max, lambda, nl, ns, partial, total_w);
+    RK_HIP(hipGetLastError());
+    rc = profile_mark(h, stream, false);
+    if (rc != ROCKET_OK) return rc;
+    const int width = total_w + h->K;
+    hipLaunchKernelGGL(rk_reduce_batch, dim3((width + 255) / 256), dim3(256), 0, stream, partial, B, width, total_w,
+                       grad_w_dev, grad_b_dev);
+    RK_HIP(hipGetLastError());
+    return ROCKET_OK;
 }

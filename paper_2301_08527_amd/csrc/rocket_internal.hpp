@@ -29,6 +29,7 @@ struct rocket_kernels {
     int64_t row_len = 0;     // floats per padded row (multiple of 64)
     double conv_fma = 0.0;   // sum_k n_k * n_ch_k * len_k
     double outputs = 0.0;    // sum_k n_k
+    int32_t max_terms = 0;   // largest n_ch * length of any kernel
 
     // device mirror (allocated on first use on `device`)
     int device = -1;

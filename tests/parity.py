@@ -49,3 +49,36 @@ def check_forward(x, kr, out_gpu, mask, lam=10.0, shift=-3.0, sel=None, rows=Non
         bad = diff > ref["ambiguous"]
         assert not bad.any(), ("ppv", np.argwhere(bad)[:5], diff.max())
     return ref
+
+
+# Gradients are sums of up to B*n (millions of) signed fp32 terms q_t*x_t, so an
+# element's error is bounded relative to the magnitude of the terms, not of the
+# (possibly cancelling) sum.  The scale used here is the largest |gradient| of
+# the same kernel: |gpu - oracle| <= G_RTOL*|oracle| + G_STOL*max_k|oracle|.
+# Measured errors sit near 1e-6 of that scale; G_STOL leaves a factor of ten.
+G_RTOL, G_STOL = 1e-4, 1e-5
+
+
+def check_backward(x, kr, gw_gpu, gb_gpu, g_soft, g_max, lam, shift, sel=None, report=None):
+    """Compares GPU gradients with the oracle for the kernels in sel (default all)."""
+    K = len(kr["length"])
+    sel = np.arange(K, dtype=np.int32) if sel is None else np.asarray(sel, np.int32)
+    gs = np.asarray(g_soft, np.float64)[:, sel]
+    gm = None if g_max is None else np.asarray(g_max, np.float64)[:, sel]
+    gw_ref, gb_ref = oracle.backward(x, kr, gs, gm, lam=lam, shift=shift, sel=sel)
+    gw_gpu = np.asarray(gw_gpu, np.float64)
+    gb_gpu = np.asarray(gb_gpu, np.float64)
+    assert np.all(np.isfinite(gw_gpu)) and np.all(np.isfinite(gb_gpu))
+    worst = 0.0
+    for k in sel:
+        lo, hi = int(kr["w_off"][k]), int(kr["w_off"][k + 1])
+        ref = np.concatenate([gw_ref[lo:hi], [gb_ref[k]]])
+        got = np.concatenate([gw_gpu[lo:hi], [gb_gpu[k]]])
+        scale = np.abs(ref).max()
+        err = np.abs(got - ref)
+        bound = G_RTOL * np.abs(ref) + G_STOL * scale + 1e-12
+        worst = max(worst, float((err / bound).max()))
+        assert np.all(err <= bound), (int(k), float(err.max()), float(scale))
+    if report is not None:
+        report["worst_ratio"] = worst
+    return gw_ref, gb_ref
