@@ -169,9 +169,9 @@ def main():
         kr = rocket.rocket_kernels_view_get(h)
         n_ex = args.cpu_examples
         if n_ex is None:
-            # aim at 10-30 s of oracle time: the oracle does roughly 0.4 GFMA/s per thread
+            # aim at 10-30 s of oracle time: the oracle does roughly 1.4 GFMA/s per thread
             import oracle
-            rate = 0.4e9 * oracle.num_threads()
+            rate = 1.4e9 * oracle.num_threads()
             n_ex = int(max(1, min(B, round(15.0 * rate / fma_per_series))))
         line["cpu_baseline"] = cpu_baseline(cfg_id, x_host, kr, mask, args.lam, n_ex)
 
