@@ -493,6 +493,26 @@ constexpr int kLdsMaxD = 8;                                       // dilations 1
 constexpr int kLdsStage = 4;                                      // staged words per lane per round
 constexpr int kLdsTileWords = ((kLdsRows * kThreads + 10 * (kLdsMaxD - 1)) / (kThreads * kLdsStage) + 1) * kThreads * kLdsStage;
 
+// Copies `nin` floats starting `chunk_bytes` into a row to the LDS tile with coalesced
+// loads (rounded up to whole rounds of kThreads*kLdsStage words: the tile and the
+// workspace slack are sized for that).  Barriers on both sides: nobody still reads the
+// previous contents, and the new contents are visible to all lanes afterwards.
+__device__ __forceinline__ void rk_stage_tile(__amdgpu_buffer_rsrc_t row, uint32_t chunk_bytes, int nin, float *tile)
+{
+    const int tid = static_cast<int>(threadIdx.x);
+    __syncthreads();
+    for (int base = 0; base < nin; base += kThreads * kLdsStage) {
+        float v[kLdsStage];
+#pragma unroll
+        for (int u = 0; u < kLdsStage; ++u)
+            v[u] = rk_load(row, static_cast<uint32_t>(tid + u * kThreads) * 4u,
+                           chunk_bytes + static_cast<uint32_t>(base) * 4u);
+#pragma unroll
+        for (int u = 0; u < kLdsStage; ++u) tile[base + tid + u * kThreads] = v[u];
+    }
+    __syncthreads();
+}
+
 template <int LEN, int D>
 __device__ __forceinline__ int rk_lds_bands(const KernelCtx &k, int rows, float *tile, PoolState &st)
 {
@@ -516,17 +536,7 @@ __device__ __forceinline__ int rk_lds_bands(const KernelCtx &k, int rows, float 
             float w[LEN];
 #pragma unroll
             for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
-            __syncthreads();   // everyone is done reading the previous channel's tile
-            for (int base = 0; base < nin; base += kThreads * kLdsStage) {
-                float v[kLdsStage];
-#pragma unroll
-                for (int u = 0; u < kLdsStage; ++u)
-                    v[u] = rk_load(row, static_cast<uint32_t>(tid + u * kThreads) * 4u,
-                                   chunk_bytes + static_cast<uint32_t>(base) * 4u);
-#pragma unroll
-                for (int u = 0; u < kLdsStage; ++u) tile[base + tid + u * kThreads] = v[u];
-            }
-            __syncthreads();
+            rk_stage_tile(row, chunk_bytes, nin, tile);
             if (active) {
                 rk_static_for<0, R + LEN - 1>([&](auto ic) {
                     constexpr int i = decltype(ic)::value;
@@ -646,15 +656,17 @@ __global__ __launch_bounds__(kThreads) void rk_forward(const float *__restrict__
 //   1. recompute the R conv outputs,
 //   2. turn them into q_i = g_soft * (lambda/n) * s_i (1 - s_i),
 //   3. per channel, re-read the strip's inputs and form the lane's share of
-//      d/dw[c][j] = sum_i q_i * x[c][t_i + j*d - p]  (R*LEN multiply-adds),
-//      then add it to a per-lane-slot accumulator in LDS (slot = lane index in
-//      its wavefront, so the four wavefronts of a workgroup share slots and use
-//      LDS atomic adds, which never collide inside one instruction).
-// At the end the slots are summed and the workgroup writes its partial gradient
-// row partial[b][...]; a second kernel sums the rows over the batch in a fixed
-// order, so the result does not depend on scheduling across workgroups.
+//      d/dw[c][j] = sum_i q_i * x[c][t_i + j*d - p]  (R*LEN multiply-adds), sum it over
+//      each row of 16 lanes with four DPP adds, and let one lane per row add the row
+//      sum to that row's own slot in LDS (16 slots per weight: 4 wavefronts x 4 rows;
+//      plain read-modify-write, no atomics, nobody else touches the slot).
+// Lanes without a strip recompute the last strip with a zero coefficient, so control
+// flow stays wavefront-uniform around the cross-lane adds.  At the end the slots are
+// summed and the workgroup writes its partial gradient row partial[b][...]; a second
+// kernel sums the rows over the batch in a fixed order, so results are deterministic.
 
 constexpr int kBwdMaxTerms = 9 * 11;     // n_ch <= 9 channels x len <= 11 weights
+constexpr int kBwdSlots = 16;            // LDS slots per weight: 4 wavefronts x 4 rows of 16 lanes
 
 struct BwdState {
     float qsum;     // per lane: sum of q (bias gradient)
@@ -673,76 +685,183 @@ __device__ __forceinline__ float rk_dsigmoid(float z, float nl, float ns)
     return sg * (e * sg);
 }
 
+// Sum over each row of 16 lanes (all 16 lanes end up with the row sum).
+__device__ __forceinline__ float rk_row16_sum(float v)
+{
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x124, 0xF, 0xF, true));  // row_ror:4
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xF, 0xF, true));  // row_ror:8
+    return v;
+}
+
+// Adds the lane shares g[0..LEN) of channel c's weight gradient to the LDS slots.
+// Must be called by all 64 lanes of the wavefront.
+template <int LEN>
+__device__ __forceinline__ void rk_bwd_deposit(float (&g)[LEN], int c, float *slots)
+{
+#pragma unroll
+    for (int j = 0; j < LEN; ++j) g[j] = rk_row16_sum(g[j]);
+    const int tid = static_cast<int>(threadIdx.x);
+    if ((tid & 15) == 0) {
+        float *slot = slots + (c * LEN) * kBwdSlots + (tid >> 4);   // (wavefront, row) = tid / 16
+#pragma unroll
+        for (int j = 0; j < LEN; ++j) slot[j * kBwdSlots] += g[j];
+    }
+}
+
 template <int LEN, int R>
 __device__ __forceinline__ void rk_bwd_segment(const KernelCtx &k, int row0, int nbands, int ncols, float coef,
                                                bool want_max, float *slots, BwdState &st)
 {
     const int nstrips = nbands * ncols;
     const uint32_t dbytes = static_cast<uint32_t>(k.d) * 4u;
-    const int lane = static_cast<int>(threadIdx.x) & 63;
-    for (int base = 0; base < nstrips; base += kThreads) {
-        const int s = base + static_cast<int>(threadIdx.x);
-        if (s < nstrips) {
-            const int band = (nbands == 1) ? 0 : s / ncols;
-            const int r = s - band * ncols;
-            const int t0 = (row0 + band * R) * k.d + r;
-            const uint32_t voff = static_cast<uint32_t>(t0) * 4u;
-            float acc[R];
+    for (int base = 0; base < nstrips; base += kThreads) {      // uniform trip count
+        const int s_raw = base + static_cast<int>(threadIdx.x);
+        const bool valid = s_raw < nstrips;
+        const int s = valid ? s_raw : nstrips - 1;              // idle lanes redo the last strip with weight 0
+        const float lane_coef = valid ? coef : 0.f;
+        const int band = (nbands == 1) ? 0 : s / ncols;
+        const int r = s - band * ncols;
+        const int t0 = (row0 + band * R) * k.d + r;
+        const uint32_t voff = static_cast<uint32_t>(t0) * 4u;
+        float acc[R];
 #pragma unroll
-            for (int i = 0; i < R; ++i) acc[i] = 0.f;
-            for (int c = 0; c < k.nch; ++c) {
-                const __amdgpu_buffer_rsrc_t row =
-                    rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
-                float w[LEN];
+        for (int i = 0; i < R; ++i) acc[i] = 0.f;
+        for (int c = 0; c < k.nch; ++c) {
+            const __amdgpu_buffer_rsrc_t row =
+                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+            float w[LEN];
 #pragma unroll
-                for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
-                rk_static_for<0, R + LEN - 1>([&](auto ic) {
-                    constexpr int i = decltype(ic)::value;
-                    rk_taps<LEN, R, i>(w, rk_load(row, voff, i * dbytes), acc);
-                });
-            }
-            if (want_max) {
-#pragma unroll
-                for (int i = 0; i < R; ++i) {
-                    if (acc[i] > st.vmax) { st.vmax = acc[i]; st.targ = t0 + i * k.d; }
-                }
-            }
+            for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
+            rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                rk_taps<LEN, R, i>(w, rk_load(row, voff, i * dbytes), acc);
+            });
+        }
+        if (want_max) {
 #pragma unroll
             for (int i = 0; i < R; ++i) {
-                acc[i] = coef * rk_dsigmoid(acc[i], k.nl, k.ns);   // acc now holds q
-                st.qsum += acc[i];
+                if (acc[i] > st.vmax) { st.vmax = acc[i]; st.targ = t0 + i * k.d; }
             }
-            for (int c = 0; c < k.nch; ++c) {
-                const __amdgpu_buffer_rsrc_t row =
-                    rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
-                float g[LEN];
+        }
 #pragma unroll
-                for (int j = 0; j < LEN; ++j) g[j] = 0.f;
-                rk_static_for<0, R + LEN - 1>([&](auto ic) {
-                    constexpr int i = decltype(ic)::value;
-                    const float xv = rk_load(row, voff, i * dbytes);
-                    rk_static_for<0, LEN>([&](auto jc) {
-                        constexpr int j = decltype(jc)::value;
-                        constexpr int o = i - j;
-                        if constexpr (o >= 0 && o < R) g[j] = fmaf(acc[o], xv, g[j]);
-                    });
+        for (int i = 0; i < R; ++i) {
+            acc[i] = lane_coef * rk_dsigmoid(acc[i], k.nl, k.ns);   // acc now holds q
+            st.qsum += acc[i];
+        }
+        for (int c = 0; c < k.nch; ++c) {
+            const __amdgpu_buffer_rsrc_t row =
+                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+            float g[LEN];
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) g[j] = 0.f;
+            rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                const float xv = rk_load(row, voff, i * dbytes);
+                rk_static_for<0, LEN>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+                    constexpr int o = i - j;
+                    if constexpr (o >= 0 && o < R) g[j] = fmaf(acc[o], xv, g[j]);
                 });
-                float *slot = slots + (c * LEN) * 64 + lane;
-#pragma unroll
-                for (int j = 0; j < LEN; ++j) atomicAdd(slot + j * 64, g[j]);
-            }
+            });
+            rk_bwd_deposit<LEN>(g, c, slots);
         }
     }
 }
 
+// LDS path of the backward pass (d < 8): the chunk's input range is staged once per
+// channel for the conv and once more for the weight gradient.
+template <int LEN, int D>
+__device__ __forceinline__ int rk_bwd_lds_bands(const KernelCtx &k, int rows, float coef, bool want_max, float *tile,
+                                                float *slots, BwdState &st)
+{
+    constexpr int R = kLdsRows;
+    const int nb = rows / R;
+    if (nb == 0) return 0;
+    constexpr int G = kThreads / D;
+    const int tid = static_cast<int>(threadIdx.x);
+    const int lane = tid & 63;
+    const int bl_raw = tid / D;
+    const int r = tid - bl_raw * D;
+    for (int band0 = 0; band0 < nb; band0 += G) {
+        const int gb = min(G, nb - band0);
+        const bool active = bl_raw < gb;
+        const int bl = active ? bl_raw : gb - 1;        // idle lanes redo the chunk's last band with weight 0
+        const float lane_coef = active ? coef : 0.f;
+        const float *mine = tile + bl * R * D + r;
+        const int nin = (gb * R + LEN - 1) * D;
+        const uint32_t chunk_bytes = static_cast<uint32_t>(band0 * R * D) * 4u;
+        float acc[R];
+#pragma unroll
+        for (int i = 0; i < R; ++i) acc[i] = 0.f;
+        for (int c = 0; c < k.nch; ++c) {
+            const __amdgpu_buffer_rsrc_t row =
+                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+            float w[LEN];
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
+            rk_stage_tile(row, chunk_bytes, nin, tile);
+            rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                rk_taps<LEN, R, i>(w, mine[i * D], acc);
+            });
+        }
+        {
+            const int t0 = ((band0 + bl) * R) * D + r;
+            if (want_max) {
+#pragma unroll
+                for (int i = 0; i < R; ++i) {
+                    if (acc[i] > st.vmax) { st.vmax = acc[i]; st.targ = t0 + i * D; }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+                acc[i] = lane_coef * rk_dsigmoid(acc[i], k.nl, k.ns);
+                st.qsum += acc[i];
+            }
+        }
+        for (int c = 0; c < k.nch; ++c) {
+            const __amdgpu_buffer_rsrc_t row =
+                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+            rk_stage_tile(row, chunk_bytes, nin, tile);
+            float g[LEN];
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) g[j] = 0.f;
+            rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                const float xv = mine[i * D];
+                rk_static_for<0, LEN>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+                    constexpr int o = i - j;
+                    if constexpr (o >= 0 && o < R) g[j] = fmaf(acc[o], xv, g[j]);
+                });
+            });
+            rk_bwd_deposit<LEN>(g, c, slots);
+        }
+    }
+    return nb * R;
+}
+
 template <int LEN>
 __device__ __forceinline__ void rk_backward_body(const KernelCtx &k, int nout, float coef, bool want_max,
-                                                 float *slots, BwdState &st)
+                                                 float *tile, float *slots, BwdState &st)
 {
     const int d = k.d;
-    const int rows = nout / d;
-    const int tail = nout - rows * d;
+    const int total_rows = nout / d;
+    const int tail = nout - total_rows * d;
     int row0 = 0;
+    switch (d) {                          // uniform per workgroup
+        case 1: row0 = rk_bwd_lds_bands<LEN, 1>(k, total_rows, coef, want_max, tile, slots, st); break;
+        case 2: row0 = rk_bwd_lds_bands<LEN, 2>(k, total_rows, coef, want_max, tile, slots, st); break;
+        case 3: row0 = rk_bwd_lds_bands<LEN, 3>(k, total_rows, coef, want_max, tile, slots, st); break;
+        case 4: row0 = rk_bwd_lds_bands<LEN, 4>(k, total_rows, coef, want_max, tile, slots, st); break;
+        case 5: row0 = rk_bwd_lds_bands<LEN, 5>(k, total_rows, coef, want_max, tile, slots, st); break;
+        case 6: row0 = rk_bwd_lds_bands<LEN, 6>(k, total_rows, coef, want_max, tile, slots, st); break;
+        case 7: row0 = rk_bwd_lds_bands<LEN, 7>(k, total_rows, coef, want_max, tile, slots, st); break;
+        default: break;
+    }
+    const int rows = total_rows - row0;   // rows left for the register path
     const int nb16 = rows >> 4;
     if (nb16) { rk_bwd_segment<LEN, 16>(k, row0, nb16, d, coef, want_max, slots, st); row0 += nb16 << 4; }
     if (rows & 8) { rk_bwd_segment<LEN, 8>(k, row0, 1, d, coef, want_max, slots, st); row0 += 8; }
@@ -765,7 +884,8 @@ __global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict_
                                                         int plane_max, float lambda, float nl, float ns,
                                                         float *__restrict__ partial, int total_w)
 {
-    __shared__ float slots[kBwdMaxTerms * 64];
+    __shared__ float tile[kLdsTileWords];
+    __shared__ float slots[kBwdMaxTerms * kBwdSlots];
     __shared__ float s_q[kWaves];
     __shared__ float s_max[kWaves];
     __shared__ int s_arg[kWaves];
@@ -787,7 +907,7 @@ __global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict_
     k.ns = fmaf(rec.bias, nl, ns);
 
     const int nterms = rec.nch * rec.len;
-    for (int i = threadIdx.x; i < nterms * 64; i += kThreads) slots[i] = 0.f;
+    for (int i = threadIdx.x; i < nterms * kBwdSlots; i += kThreads) slots[i] = 0.f;
     __syncthreads();
 
     const float *g_row = grad_out + static_cast<size_t>(b) * F * K;
@@ -799,9 +919,9 @@ __global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict_
     st.qsum = 0.f;
     st.vmax = -INFINITY;
     st.targ = 0;
-    if (rec.len == 7) rk_backward_body<7>(k, rec.nout, coef, want_max, slots, st);
-    else if (rec.len == 9) rk_backward_body<9>(k, rec.nout, coef, want_max, slots, st);
-    else rk_backward_body<11>(k, rec.nout, coef, want_max, slots, st);
+    if (rec.len == 7) rk_backward_body<7>(k, rec.nout, coef, want_max, tile, slots, st);
+    else if (rec.len == 9) rk_backward_body<9>(k, rec.nout, coef, want_max, tile, slots, st);
+    else rk_backward_body<11>(k, rec.nout, coef, want_max, tile, slots, st);
 
     // close the lane reductions: sum of q, and (max, first position) pairs
     float qsum = st.qsum, vmax = st.vmax;
@@ -815,7 +935,7 @@ __global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict_
     }
     const int wave = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0) { s_q[wave] = qsum; s_max[wave] = vmax; s_arg[wave] = targ; }
-    __syncthreads();   // also orders the LDS atomics before the slot sums below
+    __syncthreads();   // also orders the slot updates before the slot sums below
     float gq = s_q[0], gm = s_max[0];
     int ga = s_arg[0];
 #pragma unroll
@@ -828,9 +948,9 @@ __global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict_
     float *prow = partial + static_cast<size_t>(b) * (static_cast<size_t>(total_w) + K);
     const int t = static_cast<int>(threadIdx.x);
     if (t < nterms) {
-        // rotate the start so that the threads of a wavefront hit different banks
         float sum = 0.f;
-        for (int l = 0; l < 64; ++l) sum += slots[t * 64 + ((l + t) & 63)];
+#pragma unroll
+        for (int l = 0; l < kBwdSlots; ++l) sum += slots[t * kBwdSlots + l];
         if (want_max) {
             const int c = t / rec.len, j = t - c * rec.len;
             const float *xrow = reinterpret_cast<const float *>(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes);

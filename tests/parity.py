@@ -55,8 +55,14 @@ def check_forward(x, kr, out_gpu, mask, lam=10.0, shift=-3.0, sel=None, rows=Non
 # element's error is bounded relative to the magnitude of the terms, not of the
 # (possibly cancelling) sum.  The scale used here is the largest |gradient| of
 # the same kernel: |gpu - oracle| <= G_RTOL*|oracle| + G_STOL*max_k|oracle|.
-# Measured errors sit near 1e-6 of that scale; G_STOL leaves a factor of ten.
+# Measured errors sit near 1e-6 of that scale at lambda = 10.  The fp32 error of a conv
+# output (about 1e-6) enters q = g*(lambda/n)*s(1-s) through its slope lambda*(1-2s)*q,
+# so the scale term grows with lambda beyond 10.
 G_RTOL, G_STOL = 1e-4, 1e-5
+
+
+def grad_scale_tol(lam):
+    return G_STOL * max(1.0, abs(lam) / 10.0)
 
 
 def check_backward(x, kr, gw_gpu, gb_gpu, g_soft, g_max, lam, shift, sel=None, report=None):
@@ -76,7 +82,7 @@ def check_backward(x, kr, gw_gpu, gb_gpu, g_soft, g_max, lam, shift, sel=None, r
         got = np.concatenate([gw_gpu[lo:hi], [gb_gpu[k]]])
         scale = np.abs(ref).max()
         err = np.abs(got - ref)
-        bound = G_RTOL * np.abs(ref) + G_STOL * scale + 1e-12
+        bound = G_RTOL * np.abs(ref) + grad_scale_tol(lam) * scale + 1e-12
         worst = max(worst, float((err / bound).max()))
         assert np.all(err <= bound), (int(k), float(err.max()), float(scale))
     if report is not None:
