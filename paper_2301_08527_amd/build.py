@@ -24,15 +24,9 @@ def sources():
 FORBIDDEN = ("s_set_gpr_idx_on", "v_movrel", "scratch_load", "scratch_store")
 
 
-def check_device_code(verbose=False):
-    """Emits the gfx950 assembly of the kernels and fails if it holds a forbidden instruction."""
-    asm = os.path.join(CSRC, "rocket.gfx950.s")
-    cmd = [HIPCC] + DEVICE + COMMON + ["--cuda-device-only", "-S", os.path.join(CSRC, "rocket.hip"), "-o", asm]
-    if verbose:
-        print(" ".join(cmd))
-    subprocess.check_call(cmd)
+def check_device_code(asm, verbose=False):
+    """Fails if the gfx950 assembly of the kernels holds a forbidden instruction."""
     text = open(asm).read()
-    os.remove(asm)
     bad = [w for w in FORBIDDEN if w in text]
     if bad:
         raise RuntimeError("device code contains %s: a register array is indexed at run time or spilled" % bad)
@@ -45,19 +39,26 @@ def build(force=True, verbose=False):
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(s) for s in sources()):
         return LIB
     objs = []
+    tmp = os.path.join(CSRC, "_build")
+    os.makedirs(tmp, exist_ok=True)
     # the sampler must be bit-reproducible: no contraction into FMAs, no fast-math
     jobs = [
         (os.path.join(CSRC, "sampler.cpp"), [HIPCC, "-x", "c++", "-ffp-contract=off", "-fno-fast-math"] + COMMON),
-        (os.path.join(CSRC, "rocket.hip"), [HIPCC] + DEVICE + COMMON),
+        # -save-temps keeps the gfx950 assembly of the same compilation for the check below
+        (os.path.join(CSRC, "rocket.hip"), [HIPCC, "-save-temps=obj"] + DEVICE + COMMON),
     ]
     for src, cmd in jobs:
-        obj = os.path.splitext(src)[0] + ".o"
+        obj = os.path.join(tmp, os.path.splitext(os.path.basename(src))[0] + ".o")
         full = cmd + ["-c", src, "-o", obj]
         if verbose:
             print(" ".join(full))
-        subprocess.check_call(full)
+        subprocess.check_call(full, stderr=None if verbose else subprocess.DEVNULL)
         objs.append(obj)
-    check_device_code(verbose)
+    asm = [os.path.join(tmp, f) for f in os.listdir(tmp) if f.endswith(".s") and "gfx950" in f]
+    if not asm:
+        raise RuntimeError("no gfx950 assembly was produced")
+    for a in asm:
+        check_device_code(a, verbose)
     link = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     if verbose:
         print(" ".join(link))

@@ -59,6 +59,7 @@ int rk_finish_handle(rocket_kernels &h)
     h.conv_fma = 0.0;
     h.outputs = 0.0;
     h.max_terms = 0;
+    int32_t max_dil = 0;
     std::vector<double> cost(K);
     for (int32_t k = 0; k < K; ++k) {
         h.ch_off[k + 1] = h.ch_off[k] + h.n_ch[k];
@@ -67,6 +68,7 @@ int rk_finish_handle(rocket_kernels &h)
                           static_cast<int64_t>(h.length[k] - 1) * h.dilation[k];
         if (n < 1) return rk_fail(ROCKET_ESHAPE, "kernel " + std::to_string(k) + " has no output position");
         h.pad_max = std::max(h.pad_max, h.padding[k]);
+        max_dil = std::max(max_dil, h.dilation[k]);
         h.max_terms = std::max(h.max_terms, h.n_ch[k] * h.length[k]);
         cost[k] = static_cast<double>(n) * h.n_ch[k] * h.length[k];
         h.conv_fma += cost[k];
@@ -80,9 +82,11 @@ int rk_finish_handle(rocket_kernels &h)
     for (int32_t k = 0; k < K; ++k) h.order[k] = k;
     std::stable_sort(h.order.begin(), h.order.end(),
                      [&](int32_t a, int32_t b) { return cost[a] > cost[b]; });
-    // padded rows: `lead` zeros, the L samples, then at least pad_max zeros
+    // padded rows: `lead` zeros, the L samples, then zeros: at least the largest padding,
+    // and at least the largest dilation (idle lanes of a partial last row read up to one
+    // row of d floats past the series)
     h.lead = static_cast<int32_t>(round_up(h.pad_max, 64));
-    h.row_len = round_up(static_cast<int64_t>(h.lead) + h.L + h.pad_max, 64);
+    h.row_len = round_up(static_cast<int64_t>(h.lead) + h.L + std::max(h.pad_max, max_dil), 64);
     h.params_dirty = true;
     return ROCKET_OK;
 }
@@ -441,6 +445,7 @@ struct KernelCtx {
     const int32_t *chans;  // this kernel's channel list
     const float *wts;      // this kernel's weights, channel-major
     int nch, d;
+    int pad, L;            // the kernel's padding and the series length
     float negbias;         // -bias
     uint32_t mask;
     float nl, ns;          // softPPV: exp2(z*nl + ns) = exp(-(lambda*y + shift))
@@ -480,7 +485,7 @@ __device__ __forceinline__ void rk_segment(const KernelCtx &k, int row0, int nba
     }
 }
 
-// LDS path for small dilations.  With d < 64 the strips of a wavefront start
+// LDS path for small dilations (d < kLdsMaxD).  With d < 64 the strips of a wavefront start
 // kLdsRows*d floats apart, so direct loads would touch a different cache line per
 // lane group.  Instead the workgroup copies the contiguous input range of a
 // chunk of bands into LDS with coalesced loads and the lanes read their strips
@@ -488,8 +493,15 @@ __device__ __forceinline__ void rk_segment(const KernelCtx &k, int row0, int nba
 // between neighbouring bands odd (times d), which spreads the strided LDS reads
 // over the banks without padding.  D is a template parameter so that the LDS
 // read offsets i*D*4 are immediates.
-constexpr int kLdsRows = 17;
-constexpr int kLdsMaxD = 8;                                       // dilations 1..7 take this path
+#ifndef RK_LDS_ROWS
+#define RK_LDS_ROWS 17
+#endif
+#ifndef RK_LDS_MAXD
+#define RK_LDS_MAXD 16
+#endif
+constexpr int kFewMinD = 256;            // few-rows path needs at least a workgroup of columns
+constexpr int kLdsRows = RK_LDS_ROWS;
+constexpr int kLdsMaxD = RK_LDS_MAXD;                             // dilations below this take this path
 constexpr int kLdsStage = 4;                                      // staged words per lane per round
 constexpr int kLdsTileWords = ((kLdsRows * kThreads + 10 * (kLdsMaxD - 1)) / (kThreads * kLdsStage) + 1) * kThreads * kLdsStage;
 
@@ -552,6 +564,81 @@ __device__ __forceinline__ int rk_lds_bands(const KernelCtx &k, int rows, float 
     return nb * R;
 }
 
+// Pooling of one finished sum (see rk_pool).
+__device__ __forceinline__ void rk_pool1(float z, uint32_t mask, float negbias, float nl, float ns, PoolState &st)
+{
+    const float one[1] = {z};
+    rk_pool<1>(one, mask, negbias, nl, ns, st);
+}
+
+// Few-rows path for large dilations: when the whole output has at most RM rows of d
+// positions (d >= n/RM), one strip per column covers every row, so each input is
+// loaded exactly once per channel, whatever the row count (the binary band
+// decomposition would cut such a kernel into short strips with little reuse).
+// The row count is a run-time uniform: window rows past it are skipped with scalar
+// branches.  Window rows that lie entirely in the zero padding ("same" padding
+// with a large dilation puts (len-1)/2 such rows on either side) are skipped too,
+// loads and multiply-adds alike.  The partial last row is handled in the same
+// strip and masked per lane in the pooling.
+template <int LEN, int RM>
+__device__ __forceinline__ void rk_few_rows(const KernelCtx &k, int rows, int tail, PoolState &st)
+{
+    const int nrows = rows + (tail > 0 ? 1 : 0);            // rows with at least one output
+    const int prow = k.pad / k.d;                           // padding in rows: 0 or (LEN-1)/2
+    const int data_rows = (k.L + k.d - 1) / k.d;            // input rows that hold samples
+    const uint32_t dbytes = static_cast<uint32_t>(k.d) * 4u;
+    // bit i: window row i is needed (i < nrows+LEN-1) and holds samples (0 <= i-prow < data_rows)
+    uint64_t live = 0;
+    for (int i = 0; i < nrows + LEN - 1; ++i)
+        if (i >= prow && i - prow < data_rows) live |= 1ull << i;
+    for (int base = 0; base < k.d; base += kThreads) {
+        const int r = base + static_cast<int>(threadIdx.x);
+        if (r < k.d) {
+            const uint32_t voff = static_cast<uint32_t>(r) * 4u;
+            float acc[RM];
+#pragma unroll
+            for (int i = 0; i < RM; ++i) acc[i] = 0.f;
+            for (int c = 0; c < k.nch; ++c) {
+                const __amdgpu_buffer_rsrc_t row =
+                    rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+                float w[LEN];
+#pragma unroll
+                for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
+                // all loads first (so they are in flight together), then the multiply-adds
+                float xv[RM + LEN - 1];
+                rk_static_for<0, RM + LEN - 1>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    if ((live >> i) & 1) xv[i] = rk_load(row, voff, i * dbytes);
+                });
+                rk_static_for<0, RM + LEN - 1>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    if ((live >> i) & 1) rk_taps<LEN, RM, i>(w, xv[i], acc);
+                });
+            }
+            rk_static_for<0, RM>([&](auto oc) {
+                constexpr int o = decltype(oc)::value;
+                if (o < rows) {
+                    rk_pool1(acc[o], k.mask, k.negbias, k.nl, k.ns, st);
+                } else if (o == rows && r < tail) {
+                    rk_pool1(acc[o], k.mask, k.negbias, k.nl, k.ns, st);
+                }
+            });
+        }
+    }
+}
+
+// Calls rk_lds_bands<LEN, D> for the D that equals the kernel's dilation (D < kLdsMaxD).
+template <int LEN, int D>
+__device__ __forceinline__ int rk_lds_dispatch(const KernelCtx &k, int rows, float *tile, PoolState &st)
+{
+    if constexpr (D < kLdsMaxD) {
+        if (k.d == D) return rk_lds_bands<LEN, D>(k, rows, tile, st);
+        return rk_lds_dispatch<LEN, D + 1>(k, rows, tile, st);
+    } else {
+        return 0;
+    }
+}
+
 template <int LEN>
 __device__ __forceinline__ void rk_forward_body(const KernelCtx &k, int nout, float *tile, PoolState &st)
 {
@@ -559,16 +646,14 @@ __device__ __forceinline__ void rk_forward_body(const KernelCtx &k, int nout, fl
     const int rows = nout / d;            // full rows of d outputs
     const int tail = nout - rows * d;     // outputs of the partial last row
     int row0 = 0;
-    switch (d) {                          // uniform per workgroup
-        case 1: row0 = rk_lds_bands<LEN, 1>(k, rows, tile, st); break;
-        case 2: row0 = rk_lds_bands<LEN, 2>(k, rows, tile, st); break;
-        case 3: row0 = rk_lds_bands<LEN, 3>(k, rows, tile, st); break;
-        case 4: row0 = rk_lds_bands<LEN, 4>(k, rows, tile, st); break;
-        case 5: row0 = rk_lds_bands<LEN, 5>(k, rows, tile, st); break;
-        case 6: row0 = rk_lds_bands<LEN, 6>(k, rows, tile, st); break;
-        case 7: row0 = rk_lds_bands<LEN, 7>(k, rows, tile, st); break;
-        default: break;
+    // every branch below is uniform per workgroup
+    if (d >= kFewMinD) {
+        const int nrows = rows + (tail > 0 ? 1 : 0);
+        if (nrows <= 8) { rk_few_rows<LEN, 8>(k, rows, tail, st); return; }
+        if (nrows <= 16) { rk_few_rows<LEN, 16>(k, rows, tail, st); return; }
+        if (nrows <= 24) { rk_few_rows<LEN, 24>(k, rows, tail, st); return; }
     }
+    if (d < kLdsMaxD) row0 = rk_lds_dispatch<LEN, 1>(k, rows, tile, st);
     const int left = rows - row0;         // rows for the register path
 #if RK_RMAX == 32
     const int nb32 = left >> 5;
@@ -589,7 +674,7 @@ __device__ __forceinline__ void rk_forward_body(const KernelCtx &k, int nout, fl
 #if RK_WPE
 __attribute__((amdgpu_waves_per_eu(RK_WPE)))
 #endif
-__global__ __launch_bounds__(kThreads) void rk_forward(const float *__restrict__ xpad, int row_len, int lead, int C, int K,
+__global__ __launch_bounds__(kThreads) void rk_forward(const float *__restrict__ xpad, int row_len, int lead, int L, int C, int K,
                                                        const RkKernelRec *__restrict__ recs,
                                                        const int32_t *__restrict__ order,
                                                        const int32_t *__restrict__ channels,
@@ -609,6 +694,8 @@ __global__ __launch_bounds__(kThreads) void rk_forward(const float *__restrict__
     k.wts = weights + rec.w_off;
     k.nch = rec.nch;
     k.d = rec.dil;
+    k.pad = rec.pad;
+    k.L = L;
     k.negbias = -rec.bias;
     k.mask = mask;
     k.nl = nl;
@@ -843,6 +930,18 @@ __device__ __forceinline__ int rk_bwd_lds_bands(const KernelCtx &k, int rows, fl
     return nb * R;
 }
 
+template <int LEN, int D>
+__device__ __forceinline__ int rk_bwd_lds_dispatch(const KernelCtx &k, int rows, float coef, bool want_max,
+                                                   float *tile, float *slots, BwdState &st)
+{
+    if constexpr (D < kLdsMaxD) {
+        if (k.d == D) return rk_bwd_lds_bands<LEN, D>(k, rows, coef, want_max, tile, slots, st);
+        return rk_bwd_lds_dispatch<LEN, D + 1>(k, rows, coef, want_max, tile, slots, st);
+    } else {
+        return 0;
+    }
+}
+
 template <int LEN>
 __device__ __forceinline__ void rk_backward_body(const KernelCtx &k, int nout, float coef, bool want_max,
                                                  float *tile, float *slots, BwdState &st)
@@ -851,16 +950,7 @@ __device__ __forceinline__ void rk_backward_body(const KernelCtx &k, int nout, f
     const int total_rows = nout / d;
     const int tail = nout - total_rows * d;
     int row0 = 0;
-    switch (d) {                          // uniform per workgroup
-        case 1: row0 = rk_bwd_lds_bands<LEN, 1>(k, total_rows, coef, want_max, tile, slots, st); break;
-        case 2: row0 = rk_bwd_lds_bands<LEN, 2>(k, total_rows, coef, want_max, tile, slots, st); break;
-        case 3: row0 = rk_bwd_lds_bands<LEN, 3>(k, total_rows, coef, want_max, tile, slots, st); break;
-        case 4: row0 = rk_bwd_lds_bands<LEN, 4>(k, total_rows, coef, want_max, tile, slots, st); break;
-        case 5: row0 = rk_bwd_lds_bands<LEN, 5>(k, total_rows, coef, want_max, tile, slots, st); break;
-        case 6: row0 = rk_bwd_lds_bands<LEN, 6>(k, total_rows, coef, want_max, tile, slots, st); break;
-        case 7: row0 = rk_bwd_lds_bands<LEN, 7>(k, total_rows, coef, want_max, tile, slots, st); break;
-        default: break;
-    }
+    if (d < kLdsMaxD) row0 = rk_bwd_lds_dispatch<LEN, 1>(k, total_rows, coef, want_max, tile, slots, st);
     const int rows = total_rows - row0;   // rows left for the register path
     const int nb16 = rows >> 4;
     if (nb16) { rk_bwd_segment<LEN, 16>(k, row0, nb16, d, coef, want_max, slots, st); row0 += nb16 << 4; }
@@ -875,7 +965,7 @@ __device__ __forceinline__ void rk_backward_body(const KernelCtx &k, int nout, f
 // indices of the softPPV and max features in it (plane_max < 0: max not included).
 // partial is B rows of (total_w + K) floats: weight gradients in the layout of
 // `weights`, then the K bias gradients.
-__global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict__ xpad, int row_len, int lead, int C, int K,
+__global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict__ xpad, int row_len, int lead, int L, int C, int K,
                                                         const RkKernelRec *__restrict__ recs,
                                                         const int32_t *__restrict__ order,
                                                         const int32_t *__restrict__ channels,
@@ -901,6 +991,8 @@ __global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict_
     k.wts = weights + rec.w_off;
     k.nch = rec.nch;
     k.d = rec.dil;
+    k.pad = rec.pad;
+    k.L = L;
     k.negbias = -rec.bias;
     k.mask = 0;
     k.nl = nl;
@@ -1020,7 +1112,7 @@ extern "C" int rocket_transform(rocket_kernels *h, const float *x_dev, int32_t B
     rc = profile_mark(h, stream, true);
     if (rc != ROCKET_OK) return rc;
     hipLaunchKernelGGL(rk_forward, dim3(static_cast<unsigned>(B) * h->K), dim3(kThreads), 0, stream, xpad,
-                       static_cast<int>(h->row_len), h->lead, h->C, h->K, h->d_rec, h->d_order, h->d_channels,
+                       static_cast<int>(h->row_len), h->lead, h->L, h->C, h->K, h->d_rec, h->d_order, h->d_channels,
                        h->d_weights, mask, nl, ns, out_dev);
     RK_HIP(hipGetLastError());
     return profile_mark(h, stream, false);
@@ -1054,7 +1146,7 @@ extern "C" int rocket_soft_ppv_backward(rocket_kernels *h, const float *x_dev, i
     rc = profile_mark(h, stream, true);
     if (rc != ROCKET_OK) return rc;
     hipLaunchKernelGGL(rk_backward, dim3(static_cast<unsigned>(B) * h->K), dim3(kThreads), 0, stream, xpad,
-                       static_cast<int>(h->row_len), h->lead, h->C, h->K, h->d_rec, h->d_order, h->d_channels,
+                       static_cast<int>(h->row_len), h->lead, h->L, h->C, h->K, h->d_rec, h->d_order, h->d_channels,
                        h->d_weights, grad_out_dev, F, plane_soft, plane_max, lambda, nl, ns, partial, total_w);
     RK_HIP(hipGetLastError());
     rc = profile_mark(h, stream, false);
