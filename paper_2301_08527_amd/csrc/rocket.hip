@@ -388,6 +388,17 @@ __device__ __forceinline__ float rk_load(__amdgpu_buffer_rsrc_t row, uint32_t la
                                                                           static_cast<int>(uniform_bytes), 0));
 }
 
+// Advances a scalar byte offset by `step` and hides the result from the optimiser, so
+// the offsets of a strip's loads form one running scalar add per load instead of
+// dozens of precomputed multiples that would not fit the scalar register file
+// (they were spilled to vector lanes and read back once per channel).
+__device__ __forceinline__ uint32_t rk_advance(uint32_t off, uint32_t step)
+{
+    off += step;
+    asm volatile("" : "+s"(off));
+    return off;
+}
+
 // Compile-time loop: f(integral_constant<int, I>) for I in [I0, N).  Every index into
 // the per-lane accumulator and weight arrays below comes from such a constant, so the
 // arrays always live in named registers (a run-time index would make the compiler
@@ -472,9 +483,11 @@ __device__ __forceinline__ void rk_segment(const KernelCtx &k, int row0, int nba
                 float w[LEN];
 #pragma unroll
                 for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
+                uint32_t soff = 0;
                 rk_static_for<0, R + LEN - 1>([&](auto ic) {
                     constexpr int i = decltype(ic)::value;
-                    rk_taps<LEN, R, i>(w, rk_load(row, voff, i * dbytes), acc);
+                    rk_taps<LEN, R, i>(w, rk_load(row, voff, soff), acc);
+                    soff = rk_advance(soff, dbytes);
                 });
             };
 #pragma unroll
@@ -606,9 +619,11 @@ __device__ __forceinline__ void rk_few_rows(const KernelCtx &k, int rows, int ta
                 for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
                 // all loads first (so they are in flight together), then the multiply-adds
                 float xv[RM + LEN - 1];
+                uint32_t soff = 0;
                 rk_static_for<0, RM + LEN - 1>([&](auto ic) {
                     constexpr int i = decltype(ic)::value;
-                    if ((live >> i) & 1) xv[i] = rk_load(row, voff, i * dbytes);
+                    if ((live >> i) & 1) xv[i] = rk_load(row, voff, soff);
+                    soff = rk_advance(soff, dbytes);
                 });
                 rk_static_for<0, RM + LEN - 1>([&](auto ic) {
                     constexpr int i = decltype(ic)::value;
@@ -821,9 +836,11 @@ __device__ __forceinline__ void rk_bwd_segment(const KernelCtx &k, int row0, int
             float w[LEN];
 #pragma unroll
             for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
+            uint32_t soff = 0;
             rk_static_for<0, R + LEN - 1>([&](auto ic) {
                 constexpr int i = decltype(ic)::value;
-                rk_taps<LEN, R, i>(w, rk_load(row, voff, i * dbytes), acc);
+                rk_taps<LEN, R, i>(w, rk_load(row, voff, soff), acc);
+                soff = rk_advance(soff, dbytes);
             });
         }
         if (want_max) {
@@ -843,9 +860,11 @@ __device__ __forceinline__ void rk_bwd_segment(const KernelCtx &k, int row0, int
             float g[LEN];
 #pragma unroll
             for (int j = 0; j < LEN; ++j) g[j] = 0.f;
+            uint32_t soff = 0;
             rk_static_for<0, R + LEN - 1>([&](auto ic) {
                 constexpr int i = decltype(ic)::value;
-                const float xv = rk_load(row, voff, i * dbytes);
+                const float xv = rk_load(row, voff, soff);
+                soff = rk_advance(soff, dbytes);
                 rk_static_for<0, LEN>([&](auto jc) {
                     constexpr int j = decltype(jc)::value;
                     constexpr int o = i - j;
