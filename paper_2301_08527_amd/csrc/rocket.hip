@@ -601,44 +601,58 @@ __device__ __forceinline__ void rk_few_rows(const KernelCtx &k, int rows, int ta
     const int data_rows = (k.L + k.d - 1) / k.d;            // input rows that hold samples
     const uint32_t dbytes = static_cast<uint32_t>(k.d) * 4u;
     // bit i: window row i is needed (i < nrows+LEN-1) and holds samples (0 <= i-prow < data_rows)
-    uint64_t live = 0;
-    for (int i = 0; i < nrows + LEN - 1; ++i)
-        if (i >= prow && i - prow < data_rows) live |= 1ull << i;
-    for (int base = 0; base < k.d; base += kThreads) {
-        const int r = base + static_cast<int>(threadIdx.x);
-        if (r < k.d) {
-            const uint32_t voff = static_cast<uint32_t>(r) * 4u;
-            float acc[RM];
+    uint32_t live_lo = 0, live_hi = 0;
+    for (int i = 0; i < nrows + LEN - 1; ++i) {
+        if (i >= prow && i - prow < data_rows) {
+            if (i < 32) live_lo |= 1u << i;
+            else live_hi |= 1u << (i - 32);
+        }
+    }
+    // Tests bit i of the mask.  The mask is re-read through an opaque copy so that the
+    // 30-odd tests stay single scalar bit tests instead of that many precomputed
+    // (and spilled) lane masks.
+    auto is_live = [&](int i) {
+        uint32_t word = i < 32 ? live_lo : live_hi;
+        asm volatile("" : "+s"(word));
+        return ((word >> (i & 31)) & 1u) != 0;
+    };
+    for (int base = 0; base < k.d; base += kThreads) {      // uniform trip count
+        const int r_raw = base + static_cast<int>(threadIdx.x);
+        const bool lane_ok = r_raw < k.d;
+        const int r = lane_ok ? r_raw : k.d - 1;            // idle lanes shadow the last column
+        const uint32_t voff = static_cast<uint32_t>(r) * 4u;
+        float acc[RM];
 #pragma unroll
-            for (int i = 0; i < RM; ++i) acc[i] = 0.f;
-            for (int c = 0; c < k.nch; ++c) {
-                const __amdgpu_buffer_rsrc_t row =
-                    rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
-                float w[LEN];
+        for (int i = 0; i < RM; ++i) acc[i] = 0.f;
+        for (int c = 0; c < k.nch; ++c) {
+            const __amdgpu_buffer_rsrc_t row =
+                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+            float w[LEN];
 #pragma unroll
-                for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
-                // all loads first (so they are in flight together), then the multiply-adds
-                float xv[RM + LEN - 1];
-                uint32_t soff = 0;
-                rk_static_for<0, RM + LEN - 1>([&](auto ic) {
-                    constexpr int i = decltype(ic)::value;
-                    if ((live >> i) & 1) xv[i] = rk_load(row, voff, soff);
-                    soff = rk_advance(soff, dbytes);
-                });
-                rk_static_for<0, RM + LEN - 1>([&](auto ic) {
-                    constexpr int i = decltype(ic)::value;
-                    if ((live >> i) & 1) rk_taps<LEN, RM, i>(w, xv[i], acc);
-                });
-            }
-            rk_static_for<0, RM>([&](auto oc) {
-                constexpr int o = decltype(oc)::value;
-                if (o < rows) {
-                    rk_pool1(acc[o], k.mask, k.negbias, k.nl, k.ns, st);
-                } else if (o == rows && r < tail) {
-                    rk_pool1(acc[o], k.mask, k.negbias, k.nl, k.ns, st);
-                }
+            for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
+            // all loads first (so they are in flight together), then the multiply-adds
+            float xv[RM + LEN - 1];
+            uint32_t soff = 0;
+            rk_static_for<0, RM + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                if (is_live(i)) xv[i] = rk_load(row, voff, soff);
+                soff = rk_advance(soff, dbytes);
+            });
+            rk_static_for<0, RM + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                if (is_live(i)) rk_taps<LEN, RM, i>(w, xv[i], acc);
             });
         }
+        // rows below `rows` are complete; row `rows` exists only in the first `tail` columns
+        const int own_rows = lane_ok ? (rows + (r < tail ? 1 : 0)) : 0;
+        rk_static_for<0, RM>([&](auto oc) {
+            constexpr int o = decltype(oc)::value;
+            int lim = nrows;
+            asm volatile("" : "+s"(lim));
+            if (o < lim) {                                  // uniform
+                if (o < own_rows) rk_pool1(acc[o], k.mask, k.negbias, k.nl, k.ns, st);
+            }
+        });
     }
 }
 
@@ -971,8 +985,9 @@ __device__ __forceinline__ void rk_backward_body(const KernelCtx &k, int nout, f
     int row0 = 0;
     if (d < kLdsMaxD) row0 = rk_bwd_lds_dispatch<LEN, 1>(k, total_rows, coef, want_max, tile, slots, st);
     const int rows = total_rows - row0;   // rows left for the register path
-    const int nb16 = rows >> 4;
-    if (nb16) { rk_bwd_segment<LEN, 16>(k, row0, nb16, d, coef, want_max, slots, st); row0 += nb16 << 4; }
+    const int nb32 = rows >> 5;
+    if (nb32) { rk_bwd_segment<LEN, 32>(k, row0, nb32, d, coef, want_max, slots, st); row0 += nb32 << 5; }
+    if (rows & 16) { rk_bwd_segment<LEN, 16>(k, row0, 1, d, coef, want_max, slots, st); row0 += 16; }
     if (rows & 8) { rk_bwd_segment<LEN, 8>(k, row0, 1, d, coef, want_max, slots, st); row0 += 8; }
     if (rows & 4) { rk_bwd_segment<LEN, 4>(k, row0, 1, d, coef, want_max, slots, st); row0 += 4; }
     if (rows & 2) { rk_bwd_segment<LEN, 2>(k, row0, 1, d, coef, want_max, slots, st); row0 += 2; }
