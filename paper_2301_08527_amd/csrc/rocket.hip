@@ -832,13 +832,17 @@ __device__ __forceinline__ void rk_bwd_segment(const KernelCtx &k, int row0, int
 {
     const int nstrips = nbands * ncols;
     const uint32_t dbytes = static_cast<uint32_t>(k.d) * 4u;
-    for (int base = 0; base < nstrips; base += kThreads) {      // uniform trip count
+    const int step_band = kThreads / ncols, step_r = kThreads - step_band * ncols;   // uniform
+    int band_run = (nbands == 1) ? 0 : static_cast<int>(threadIdx.x) / ncols;
+    int r_run = static_cast<int>(threadIdx.x) - band_run * ncols;
+    for (int base = 0; base < nstrips; base += kThreads, band_run += step_band, r_run += step_r) {   // uniform trip count
+        if (r_run >= ncols) { r_run -= ncols; ++band_run; }
         const int s_raw = base + static_cast<int>(threadIdx.x);
         const bool valid = s_raw < nstrips;
-        const int s = valid ? s_raw : nstrips - 1;              // idle lanes redo the last strip with weight 0
         const float lane_coef = valid ? coef : 0.f;
-        const int band = (nbands == 1) ? 0 : s / ncols;
-        const int r = s - band * ncols;
+        // idle lanes redo the segment's last strip with weight 0
+        const int band = valid ? band_run : nbands - 1;
+        const int r = valid ? r_run : ncols - 1;
         const int t0 = (row0 + band * R) * k.d + r;
         const uint32_t voff = static_cast<uint32_t>(t0) * 4u;
         float acc[R];
