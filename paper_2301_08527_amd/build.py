@@ -14,9 +14,13 @@ COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+KERNEL_TUS = ("rocket_forward.hip", "rocket_backward.hip")   # translation units that hold device code
+HOST_TUS = ("rocket_api.hip",)
+
+
 def sources():
-    return [os.path.join(CSRC, f) for f in ("sampler.cpp", "rocket.hip", "rocket_internal.hpp")] + \
-           [os.path.join(ROOT, "include", "rocket.h")]
+    names = ("sampler.cpp", "rocket_internal.hpp", "rocket_device.hpp") + KERNEL_TUS + HOST_TUS
+    return [os.path.join(CSRC, f) for f in names] + [os.path.join(ROOT, "include", "rocket.h")]
 
 
 # Instructions that must not appear in the kernels: indirect register-file indexing
@@ -38,24 +42,29 @@ def check_device_code(asm, verbose=False):
 def build(force=True, verbose=False):
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(s) for s in sources()):
         return LIB
-    objs = []
     tmp = os.path.join(CSRC, "_build")
     os.makedirs(tmp, exist_ok=True)
+    for f in os.listdir(tmp):
+        if f.endswith(".s") or f.endswith(".o"):
+            os.remove(os.path.join(tmp, f))
     # the sampler must be bit-reproducible: no contraction into FMAs, no fast-math
-    jobs = [
-        (os.path.join(CSRC, "sampler.cpp"), [HIPCC, "-x", "c++", "-ffp-contract=off", "-fno-fast-math"] + COMMON),
-        # -save-temps keeps the gfx950 assembly of the same compilation for the check below
-        (os.path.join(CSRC, "rocket.hip"), [HIPCC, "-save-temps=obj"] + DEVICE + COMMON),
-    ]
-    for src, cmd in jobs:
+    jobs = [(os.path.join(CSRC, "sampler.cpp"), [HIPCC, "-x", "c++", "-ffp-contract=off", "-fno-fast-math"] + COMMON)]
+    # -save-temps keeps the gfx950 assembly of the same compilation for the check below
+    jobs += [(os.path.join(CSRC, f), [HIPCC, "-save-temps=obj"] + DEVICE + COMMON) for f in KERNEL_TUS]
+    jobs += [(os.path.join(CSRC, f), [HIPCC] + DEVICE + COMMON) for f in HOST_TUS]
+    objs, procs = [], []
+    for src, cmd in jobs:           # the translation units compile side by side
         obj = os.path.join(tmp, os.path.splitext(os.path.basename(src))[0] + ".o")
         full = cmd + ["-c", src, "-o", obj]
         if verbose:
             print(" ".join(full))
-        subprocess.check_call(full, stderr=None if verbose else subprocess.DEVNULL)
+        procs.append((full, subprocess.Popen(full, stderr=None if verbose else subprocess.DEVNULL)))
         objs.append(obj)
+    for full, p in procs:
+        if p.wait() != 0:
+            raise subprocess.CalledProcessError(p.returncode, full)
     asm = [os.path.join(tmp, f) for f in os.listdir(tmp) if f.endswith(".s") and "gfx950" in f]
-    if not asm:
+    if len(asm) < len(KERNEL_TUS):
         raise RuntimeError("no gfx950 assembly was produced")
     for a in asm:
         check_device_code(a, verbose)

@@ -1,0 +1,415 @@
+// ROCKET transform for MI355X (gfx950): C-ABI entry points (handles, validation,
+// device mirror, launch sequencing).  The kernels live in rocket_forward.hip and
+// rocket_backward.hip.  See include/rocket.h for the contract of every entry point.
+//
+// Work decomposition of the forward pass (paper section 3, parts (1)-(2)):
+//   one workgroup (256 lanes) owns one (series b, kernel k) pair and produces
+//   its pooled features, so no cross-workgroup combine is needed.
+//   The n outputs of a kernel with dilation d are viewed as a grid of rows of d
+//   consecutive positions: t = m*d + r.  A lane owns a vertical strip of R rows
+//   in one column r, i.e. outputs t0, t0+d, ..., t0+(R-1)d.  Those R outputs
+//   read the R+len-1 inputs x[t0-p+i*d]; each input is loaded once and feeds up
+//   to len fused multiply-adds from registers.  Neighbouring lanes own
+//   neighbouring columns, so every load instruction of a wavefront reads
+//   consecutive floats.  The row range is cut into bands of 16, 8, 4, 2 and 1
+//   rows (binary decomposition of the row count) plus the partial last row, so
+//   every strip is fully valid and the pooling needs no masks.
+//   Weights are wavefront-uniform (scalar registers); max / PPV count / softPPV
+//   sum stay in registers and are closed with wavefront shuffles.
+//   The batch is first copied into a zero-padded workspace so that no dilated
+//   read leaves its row and "same" padding needs no bounds checks.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <type_traits>
+
+#include "rocket_internal.hpp"
+
+// ------------------------------------------------------------------ errors
+
+static thread_local std::string g_last_error;
+
+void rk_set_error(const std::string &msg) { g_last_error = msg; }
+
+int rk_fail(int code, const std::string &msg)
+{
+    g_last_error = msg;
+    return code;
+}
+
+#define RK_HIP(call)                                                                   \
+    do {                                                                               \
+        hipError_t e_ = (call);                                                        \
+        if (e_ != hipSuccess)                                                          \
+            return rk_fail(ROCKET_EHIP, std::string(#call) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+// ------------------------------------------------------------------ host plan
+
+static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+int rk_finish_handle(rocket_kernels &h)
+{
+    const int32_t K = h.K;
+    h.ch_off.assign(K + 1, 0);
+    h.w_off.assign(K + 1, 0);
+    h.pad_max = 0;
+    h.conv_fma = 0.0;
+    h.outputs = 0.0;
+    h.max_terms = 0;
+    int32_t max_dil = 0;
+    std::vector<double> cost(K);
+    for (int32_t k = 0; k < K; ++k) {
+        h.ch_off[k + 1] = h.ch_off[k] + h.n_ch[k];
+        h.w_off[k + 1] = h.w_off[k] + static_cast<int64_t>(h.n_ch[k]) * h.length[k];
+        const int64_t n = static_cast<int64_t>(h.L) + 2LL * h.padding[k] -
+                          static_cast<int64_t>(h.length[k] - 1) * h.dilation[k];
+        if (n < 1) return rk_fail(ROCKET_ESHAPE, "kernel " + std::to_string(k) + " has no output position");
+        h.pad_max = std::max(h.pad_max, h.padding[k]);
+        max_dil = std::max(max_dil, h.dilation[k]);
+        h.max_terms = std::max(h.max_terms, h.n_ch[k] * h.length[k]);
+        cost[k] = static_cast<double>(n) * h.n_ch[k] * h.length[k];
+        h.conv_fma += cost[k];
+        h.outputs += static_cast<double>(n);
+    }
+    if (h.w_off[K] > INT32_MAX || h.ch_off[K] > INT32_MAX)
+        return rk_fail(ROCKET_EINVAL, "too many weights for 32-bit offsets");
+    // launch order: most expensive kernels first, so the last workgroups to
+    // start are the cheapest and the tail of the launch is short
+    h.order.resize(K);
+    for (int32_t k = 0; k < K; ++k) h.order[k] = k;
+    std::stable_sort(h.order.begin(), h.order.end(),
+                     [&](int32_t a, int32_t b) { return cost[a] > cost[b]; });
+    // padded rows: `lead` zeros, the L samples, then zeros: at least the largest padding,
+    // and at least the largest dilation (idle lanes of a partial last row read up to one
+    // row of d floats past the series)
+    h.lead = static_cast<int32_t>(round_up(h.pad_max, 64));
+    h.row_len = round_up(static_cast<int64_t>(h.lead) + h.L + std::max(h.pad_max, max_dil), 64);
+    h.params_dirty = true;
+    return ROCKET_OK;
+}
+
+// ------------------------------------------------------------------ handles
+
+extern "C" const char *rocket_last_error(void) { return g_last_error.c_str(); }
+
+extern "C" int32_t rocket_num_features(uint32_t mask)
+{
+    if (mask == 0 || (mask & ~7u)) return 0;
+    return static_cast<int32_t>(__builtin_popcount(mask));
+}
+
+extern "C" int rocket_make_kernels(uint64_t seed, int32_t K, int32_t C, int32_t L, rocket_kernels **out)
+{
+    if (!out) return rk_fail(ROCKET_EINVAL, "rocket_make_kernels: out is NULL");
+    *out = nullptr;
+    if (K < 1 || C < 1) return rk_fail(ROCKET_EINVAL, "rocket_make_kernels: K and C must be >= 1");
+    if (L < 11) return rk_fail(ROCKET_EINVAL, "rocket_make_kernels: L must be >= 11");
+    rocket_kernels *h = new (std::nothrow) rocket_kernels;
+    if (!h) return rk_fail(ROCKET_ENOMEM, "rocket_make_kernels: out of host memory");
+    try {
+        h->K = K; h->C = C; h->L = L;
+        rk_sample_kernels(seed, *h);
+        int rc = rk_finish_handle(*h);
+        if (rc != ROCKET_OK) { delete h; return rc; }
+    } catch (const std::bad_alloc &) {
+        delete h;
+        return rk_fail(ROCKET_ENOMEM, "rocket_make_kernels: out of host memory");
+    }
+    *out = h;
+    return ROCKET_OK;
+}
+
+extern "C" int rocket_kernels_import(int32_t K, int32_t C, int32_t L,
+                                     const int32_t *length, const int32_t *dilation, const int32_t *padding,
+                                     const float *bias, const int32_t *n_ch, const int32_t *channels,
+                                     const float *weights, rocket_kernels **out)
+{
+    if (!out) return rk_fail(ROCKET_EINVAL, "rocket_kernels_import: out is NULL");
+    *out = nullptr;
+    if (!length || !dilation || !padding || !bias || !n_ch || !channels || !weights)
+        return rk_fail(ROCKET_EINVAL, "rocket_kernels_import: NULL array");
+    if (K < 1 || C < 1 || L < 1) return rk_fail(ROCKET_EINVAL, "rocket_kernels_import: K, C, L must be >= 1");
+    rocket_kernels *h = new (std::nothrow) rocket_kernels;
+    if (!h) return rk_fail(ROCKET_ENOMEM, "rocket_kernels_import: out of host memory");
+    try {
+        h->K = K; h->C = C; h->L = L;
+        int64_t nc = 0, nw = 0;
+        std::vector<char> seen(C);
+        for (int32_t k = 0; k < K; ++k) {
+            const std::string who = "rocket_kernels_import: kernel " + std::to_string(k);
+            const int32_t len = length[k], d = dilation[k], p = padding[k], m = n_ch[k];
+            if (len != 7 && len != 9 && len != 11) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": length not in {7,9,11}"); }
+            if (d < 1) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": dilation < 1"); }
+            const int64_t span = static_cast<int64_t>(len - 1) * d;
+            if (p != 0 && p != span / 2) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": padding is neither 0 nor (len-1)d/2"); }
+            if (static_cast<int64_t>(L) + 2LL * p - span < 1) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": no output position"); }
+            if (m < 1 || m > C) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": n_ch outside [1,C]"); }
+            std::fill(seen.begin(), seen.end(), 0);
+            for (int32_t c = 0; c < m; ++c) {
+                const int32_t ch = channels[nc + c];
+                if (ch < 0 || ch >= C || seen[ch]) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": channel out of range or repeated"); }
+                seen[ch] = 1;
+            }
+            if (!std::isfinite(bias[k])) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": bias not finite"); }
+            for (int64_t i = 0; i < static_cast<int64_t>(m) * len; ++i)
+                if (!std::isfinite(weights[nw + i])) { delete h; return rk_fail(ROCKET_ESHAPE, who + ": weight not finite"); }
+            nc += m;
+            nw += static_cast<int64_t>(m) * len;
+        }
+        h->length.assign(length, length + K);
+        h->dilation.assign(dilation, dilation + K);
+        h->padding.assign(padding, padding + K);
+        h->n_ch.assign(n_ch, n_ch + K);
+        h->bias.assign(bias, bias + K);
+        h->channels.assign(channels, channels + nc);
+        h->weights.assign(weights, weights + nw);
+        int rc = rk_finish_handle(*h);
+        if (rc != ROCKET_OK) { delete h; return rc; }
+    } catch (const std::bad_alloc &) {
+        delete h;
+        return rk_fail(ROCKET_ENOMEM, "rocket_kernels_import: out of host memory");
+    }
+    *out = h;
+    return ROCKET_OK;
+}
+
+extern "C" int rocket_kernels_view_get(const rocket_kernels *h, rocket_kernels_view *v)
+{
+    if (!h || !v) return rk_fail(ROCKET_EINVAL, "rocket_kernels_view_get: NULL argument");
+    v->K = h->K; v->C = h->C; v->L = h->L;
+    v->total_channels = h->ch_off[h->K];
+    v->total_weights = h->w_off[h->K];
+    v->length = h->length.data(); v->dilation = h->dilation.data(); v->padding = h->padding.data();
+    v->n_ch = h->n_ch.data(); v->bias = h->bias.data();
+    v->ch_off = h->ch_off.data(); v->w_off = h->w_off.data();
+    v->channels = h->channels.data(); v->weights = h->weights.data();
+    return ROCKET_OK;
+}
+
+extern "C" int rocket_kernels_set_params(rocket_kernels *h, const float *weights, const float *bias)
+{
+    if (!h) return rk_fail(ROCKET_EINVAL, "rocket_kernels_set_params: NULL handle");
+    if (weights) {
+        for (size_t i = 0; i < h->weights.size(); ++i)
+            if (!std::isfinite(weights[i])) return rk_fail(ROCKET_EINVAL, "rocket_kernels_set_params: weight not finite");
+        std::copy(weights, weights + h->weights.size(), h->weights.begin());
+    }
+    if (bias) {
+        for (int32_t k = 0; k < h->K; ++k)
+            if (!std::isfinite(bias[k])) return rk_fail(ROCKET_EINVAL, "rocket_kernels_set_params: bias not finite");
+        std::copy(bias, bias + h->K, h->bias.begin());
+    }
+    h->params_dirty = true;
+    return ROCKET_OK;
+}
+
+extern "C" int rocket_work_per_series(const rocket_kernels *h, double *conv_fma, double *outputs)
+{
+    if (!h) return rk_fail(ROCKET_EINVAL, "rocket_work_per_series: NULL handle");
+    if (conv_fma) *conv_fma = h->conv_fma;
+    if (outputs) *outputs = h->outputs;
+    return ROCKET_OK;
+}
+
+static void drop_events(rocket_kernels *h)
+{
+    for (auto &pr : h->events) {
+        (void)hipEventDestroy(static_cast<hipEvent_t>(pr.first));
+        (void)hipEventDestroy(static_cast<hipEvent_t>(pr.second));
+    }
+    h->events.clear();
+}
+
+extern "C" int rocket_profile_enable(rocket_kernels *h, int enable)
+{
+    if (!h) return rk_fail(ROCKET_EINVAL, "rocket_profile_enable: NULL handle");
+    h->profile = enable != 0;
+    if (!h->profile) drop_events(h);
+    return ROCKET_OK;
+}
+
+extern "C" int rocket_profile_read(rocket_kernels *h, int32_t *launches, double *total_ms)
+{
+    if (!h || !launches || !total_ms) return rk_fail(ROCKET_EINVAL, "rocket_profile_read: NULL argument");
+    double sum = 0.0;
+    for (auto &pr : h->events) {
+        float ms = 0.f;
+        RK_HIP(hipEventSynchronize(static_cast<hipEvent_t>(pr.second)));
+        RK_HIP(hipEventElapsedTime(&ms, static_cast<hipEvent_t>(pr.first), static_cast<hipEvent_t>(pr.second)));
+        sum += ms;
+    }
+    *launches = static_cast<int32_t>(h->events.size());
+    *total_ms = sum;
+    drop_events(h);
+    return ROCKET_OK;
+}
+
+// Records the first / second event of a pair on `stream` when profiling is on.
+static int profile_mark(rocket_kernels *h, hipStream_t stream, bool begin)
+{
+    if (!h->profile) return ROCKET_OK;
+    hipEvent_t ev;
+    RK_HIP(hipEventCreate(&ev));
+    if (begin) h->events.emplace_back(ev, nullptr);
+    else h->events.back().second = ev;
+    RK_HIP(hipEventRecord(ev, stream));
+    return ROCKET_OK;
+}
+
+extern "C" void rocket_free_kernels(rocket_kernels *h)
+{
+    if (!h) return;
+    drop_events(h);
+    if (h->d_blob) {
+        int cur = -1;
+        if (hipGetDevice(&cur) == hipSuccess && cur != h->device && hipSetDevice(h->device) == hipSuccess) {
+            (void)hipFree(h->d_blob);
+            (void)hipSetDevice(cur);
+        } else {
+            (void)hipFree(h->d_blob);
+        }
+    }
+    delete h;
+}
+
+// workspace layout: [padded batch: B*C*row_len floats][backward: B*(total_w + 2K) floats]
+static size_t padded_batch_bytes(const rocket_kernels *h, int32_t B)
+{
+    // 8 KB of slack: the LDS staging of the last row may read a few hundred floats past it
+    return static_cast<size_t>(round_up(static_cast<int64_t>(B) * h->C * h->row_len * 4 + 8192, 256));
+}
+
+static size_t backward_partial_floats(const rocket_kernels *h) { return static_cast<size_t>(h->w_off[h->K]) + h->K; }
+
+extern "C" size_t rocket_workspace_bytes(const rocket_kernels *h, int32_t B, uint32_t mask, int backward)
+{
+    if (!h || B < 1 || rocket_num_features(mask) == 0) return 0;
+    size_t bytes = padded_batch_bytes(h, B);
+    if (backward) bytes += static_cast<size_t>(B) * backward_partial_floats(h) * 4;
+    return bytes;
+}
+
+// ------------------------------------------------------------------ device mirror
+
+static int ensure_device(rocket_kernels *h, hipStream_t stream)
+{
+    int cur = 0;
+    RK_HIP(hipGetDevice(&cur));
+    const int32_t K = h->K;
+    const size_t rec_b = round_up(static_cast<int64_t>(K) * sizeof(RkKernelRec), 256);
+    const size_t ord_b = round_up(static_cast<int64_t>(K) * 4, 256);
+    const size_t ch_b = round_up(static_cast<int64_t>(h->channels.size()) * 4, 256);
+    const size_t w_b = round_up(static_cast<int64_t>(h->weights.size()) * 4, 256);
+    if (h->d_blob && h->device != cur)
+        return rk_fail(ROCKET_EINVAL, "handle was first used on another device");
+    if (!h->d_blob) {
+        h->blob_bytes = rec_b + ord_b + ch_b + w_b;
+        RK_HIP(hipMalloc(&h->d_blob, h->blob_bytes));
+        h->device = cur;
+        char *base = static_cast<char *>(h->d_blob);
+        h->d_rec = reinterpret_cast<const RkKernelRec *>(base);
+        h->d_order = reinterpret_cast<const int32_t *>(base + rec_b);
+        h->d_channels = reinterpret_cast<const int32_t *>(base + rec_b + ord_b);
+        h->d_weights = reinterpret_cast<float *>(base + rec_b + ord_b + ch_b);
+        h->params_dirty = true;
+    }
+    if (h->params_dirty) {
+        std::vector<RkKernelRec> rec(K);
+        for (int32_t k = 0; k < K; ++k) {
+            RkKernelRec &r = rec[k];
+            r.len = h->length[k]; r.dil = h->dilation[k]; r.pad = h->padding[k];
+            r.nout = h->L + 2 * h->padding[k] - (h->length[k] - 1) * h->dilation[k];
+            r.bias = h->bias[k]; r.nch = h->n_ch[k];
+            r.ch_off = static_cast<int32_t>(h->ch_off[k]);
+            r.w_off = static_cast<int32_t>(h->w_off[k]);
+        }
+        // pageable sources: these copies return once the source has been read
+        RK_HIP(hipMemcpyAsync(const_cast<RkKernelRec *>(h->d_rec), rec.data(), K * sizeof(RkKernelRec), hipMemcpyHostToDevice, stream));
+        RK_HIP(hipMemcpyAsync(const_cast<int32_t *>(h->d_order), h->order.data(), K * 4, hipMemcpyHostToDevice, stream));
+        RK_HIP(hipMemcpyAsync(const_cast<int32_t *>(h->d_channels), h->channels.data(), h->channels.size() * 4, hipMemcpyHostToDevice, stream));
+        RK_HIP(hipMemcpyAsync(h->d_weights, h->weights.data(), h->weights.size() * 4, hipMemcpyHostToDevice, stream));
+        RK_HIP(hipStreamSynchronize(stream));
+        h->params_dirty = false;
+    }
+    return ROCKET_OK;
+}
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kBwdMaxTerms = 9 * 11;     // the backward kernel holds at most 9 channels x 11 weights per kernel
+
+// ------------------------------------------------------------------ launches
+
+static int check_common(const char *fn, const rocket_kernels *h, const void *x, int32_t B, uint32_t mask,
+                        float lambda, float shift, const void *ws, size_t ws_bytes, int backward)
+{
+    const std::string who(fn);
+    if (!h) return rk_fail(ROCKET_EINVAL, who + ": NULL handle");
+    if (!x) return rk_fail(ROCKET_EINVAL, who + ": x_dev is NULL");
+    if (B < 1) return rk_fail(ROCKET_EINVAL, who + ": B must be >= 1");
+    if (rocket_num_features(mask) == 0) return rk_fail(ROCKET_EINVAL, who + ": feature mask must be a non-empty subset of 7");
+    if (!std::isfinite(lambda) || !std::isfinite(shift)) return rk_fail(ROCKET_EINVAL, who + ": lambda and shift must be finite");
+    if (static_cast<int64_t>(B) * h->K > INT32_MAX) return rk_fail(ROCKET_EINVAL, who + ": B*K exceeds the grid limit");
+    const size_t need = rocket_workspace_bytes(h, B, mask, backward);
+    if (!ws || ws_bytes < need)
+        return rk_fail(ROCKET_EWORKSPACE, who + ": workspace of " + std::to_string(need) + " bytes required");
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return rk_fail(ROCKET_EWORKSPACE, who + ": workspace must be 256-byte aligned");
+    return ROCKET_OK;
+}
+
+extern "C" int rocket_transform(rocket_kernels *h, const float *x_dev, int32_t B, uint32_t mask, float lambda,
+                                float shift, float *out_dev, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_common("rocket_transform", h, x_dev, B, mask, lambda, shift, ws, ws_bytes, 0);
+    if (rc != ROCKET_OK) return rc;
+    if (!out_dev) return rk_fail(ROCKET_EINVAL, "rocket_transform: out_dev is NULL");
+    if (h->row_len > INT32_MAX) return rk_fail(ROCKET_EINVAL, "rocket_transform: series too long");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    rc = ensure_device(h, stream);
+    if (rc != ROCKET_OK) return rc;
+    float *xpad = static_cast<float *>(ws);
+    if (rk_launch_pad(h, x_dev, B, xpad, stream) != ROCKET_OK) return rk_fail(ROCKET_EHIP, "launch of the padding kernel failed");
+    const float nl = -lambda * kLog2e, ns = -shift * kLog2e;
+    rc = profile_mark(h, stream, true);
+    if (rc != ROCKET_OK) return rc;
+    if (rk_launch_forward(h, xpad, B, mask, nl, ns, out_dev, stream) != ROCKET_OK)
+        return rk_fail(ROCKET_EHIP, "launch of the forward kernel failed");
+    return profile_mark(h, stream, false);
+}
+
+extern "C" int rocket_soft_ppv_backward(rocket_kernels *h, const float *x_dev, int32_t B, uint32_t mask,
+                                        const float *grad_out_dev, float lambda, float shift, int include_max,
+                                        float *grad_w_dev, float *grad_b_dev, void *ws, size_t ws_bytes,
+                                        void *hip_stream)
+{
+    int rc = check_common("rocket_soft_ppv_backward", h, x_dev, B, mask, lambda, shift, ws, ws_bytes, 1);
+    if (rc != ROCKET_OK) return rc;
+    if (!(mask & ROCKET_F_SOFTPPV)) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: mask must contain ROCKET_F_SOFTPPV");
+    if (include_max && !(mask & ROCKET_F_MAX)) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: include_max needs ROCKET_F_MAX in the mask");
+    if (!grad_out_dev || !grad_w_dev || !grad_b_dev) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: NULL gradient pointer");
+    if (h->row_len > INT32_MAX) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: series too long");
+    if (h->max_terms > kBwdMaxTerms)
+        return rk_fail(ROCKET_ESHAPE, "rocket_soft_ppv_backward: a kernel has more than 9 channels x 11 weights");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    rc = ensure_device(h, stream);
+    if (rc != ROCKET_OK) return rc;
+    float *xpad = static_cast<float *>(ws);
+    float *partial = reinterpret_cast<float *>(static_cast<char *>(ws) + padded_batch_bytes(h, B));
+    if (rk_launch_pad(h, x_dev, B, xpad, stream) != ROCKET_OK) return rk_fail(ROCKET_EHIP, "launch of the padding kernel failed");
+    const int F = rocket_num_features(mask);
+    const int plane_soft = F - 1;                 // planes are in bit order: softPPV is last
+    const int plane_max = include_max ? 0 : -1;   // and max, when present, is first
+    const float nl = -lambda * kLog2e, ns = -shift * kLog2e;
+    rc = profile_mark(h, stream, true);
+    if (rc != ROCKET_OK) return rc;
+    if (rk_launch_backward(h, xpad, B, grad_out_dev, F, plane_soft, plane_max, lambda, nl, ns, partial, stream) != ROCKET_OK)
+        return rk_fail(ROCKET_EHIP, "launch of the backward kernel failed");
+    rc = profile_mark(h, stream, false);
+    if (rc != ROCKET_OK) return rc;
+    if (rk_launch_reduce_batch(h, partial, B, grad_w_dev, grad_b_dev, stream) != ROCKET_OK)
+        return rk_fail(ROCKET_EHIP, "launch of the batch reduction kernel failed");
+    return ROCKET_OK;
+}

@@ -1,0 +1,354 @@
+// ROCKET transform for MI355X (gfx950): soft-PPV backward kernels and their launcher.
+// See include/rocket.h for the contract of rocket_soft_ppv_backward.
+#include "rocket_device.hpp"
+
+// ------------------------------------------------------------------ backward kernels
+//
+// Backward pass through softPPV (and, optionally, the max): one workgroup per
+// (series, kernel), the same strip decomposition as the forward pass.  Per strip:
+//   1. recompute the R conv outputs,
+//   2. turn them into q_i = g_soft * (lambda/n) * s_i (1 - s_i),
+//   3. per channel, re-read the strip's inputs and form the lane's share of
+//      d/dw[c][j] = sum_i q_i * x[c][t_i + j*d - p]  (R*LEN multiply-adds), sum it over
+//      each row of 16 lanes with four DPP adds, and let one lane per row add the row
+//      sum to that row's own slot in LDS (16 slots per weight: 4 wavefronts x 4 rows;
+//      plain read-modify-write, no atomics, nobody else touches the slot).
+// Lanes without a strip recompute the last strip with a zero coefficient, so control
+// flow stays wavefront-uniform around the cross-lane adds.  At the end the slots are
+// summed and the workgroup writes its partial gradient row partial[b][...]; a second
+// kernel sums the rows over the batch in a fixed order, so results are deterministic.
+
+constexpr int kBwdMaxTerms = 9 * 11;     // n_ch <= 9 channels x len <= 11 weights
+constexpr int kBwdSlots = 16;            // LDS slots per weight: 4 wavefronts x 4 rows of 16 lanes
+
+struct BwdState {
+    float qsum;     // per lane: sum of q (bias gradient)
+    float vmax;     // per lane: running max of z = y - bias
+    int targ;       // per lane: first position attaining vmax
+};
+
+// softPPV derivative factor: given z = y - bias returns s(1-s) with
+// s = 1/(1+e), e = exp(-(lambda*y+shift)) = exp2(z*nl + ns).  The exponent is capped so
+// that e stays finite; 1-s is formed as e*s, which keeps its relative accuracy
+// when s is close to 1.
+__device__ __forceinline__ float rk_dsigmoid(float z, float nl, float ns)
+{
+    const float e = __builtin_amdgcn_exp2f(fminf(fmaf(z, nl, ns), 80.f));
+    const float sg = __builtin_amdgcn_rcpf(1.f + e);
+    return sg * (e * sg);
+}
+
+// Sum over each row of 16 lanes (all 16 lanes end up with the row sum).
+__device__ __forceinline__ float rk_row16_sum(float v)
+{
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x124, 0xF, 0xF, true));  // row_ror:4
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x128, 0xF, 0xF, true));  // row_ror:8
+    return v;
+}
+
+// Adds the lane shares g[0..LEN) of channel c's weight gradient to the LDS slots.
+// Must be called by all 64 lanes of the wavefront.
+template <int LEN>
+__device__ __forceinline__ void rk_bwd_deposit(float (&g)[LEN], int c, float *slots)
+{
+#pragma unroll
+    for (int j = 0; j < LEN; ++j) g[j] = rk_row16_sum(g[j]);
+    const int tid = static_cast<int>(threadIdx.x);
+    if ((tid & 15) == 0) {
+        float *slot = slots + (c * LEN) * kBwdSlots + (tid >> 4);   // (wavefront, row) = tid / 16
+#pragma unroll
+        for (int j = 0; j < LEN; ++j) slot[j * kBwdSlots] += g[j];
+    }
+}
+
+template <int LEN, int R>
+__device__ __forceinline__ void rk_bwd_segment(const KernelCtx &k, int row0, int nbands, int ncols, float coef,
+                                               bool want_max, float *slots, BwdState &st)
+{
+    const int nstrips = nbands * ncols;
+    const uint32_t dbytes = static_cast<uint32_t>(k.d) * 4u;
+    const int step_band = kThreads / ncols, step_r = kThreads - step_band * ncols;   // uniform
+    int band_run = (nbands == 1) ? 0 : static_cast<int>(threadIdx.x) / ncols;
+    int r_run = static_cast<int>(threadIdx.x) - band_run * ncols;
+    for (int base = 0; base < nstrips; base += kThreads, band_run += step_band, r_run += step_r) {   // uniform trip count
+        if (r_run >= ncols) { r_run -= ncols; ++band_run; }
+        const int s_raw = base + static_cast<int>(threadIdx.x);
+        const bool valid = s_raw < nstrips;
+        const float lane_coef = valid ? coef : 0.f;
+        // idle lanes redo the segment's last strip with weight 0
+        const int band = valid ? band_run : nbands - 1;
+        const int r = valid ? r_run : ncols - 1;
+        const int t0 = (row0 + band * R) * k.d + r;
+        const uint32_t voff = static_cast<uint32_t>(t0) * 4u;
+        float acc[R];
+#pragma unroll
+        for (int i = 0; i < R; ++i) acc[i] = 0.f;
+        for (int c = 0; c < k.nch; ++c) {
+            const __amdgpu_buffer_rsrc_t row =
+                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+            float w[LEN];
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
+            uint32_t soff = 0;
+            rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                rk_taps<LEN, R, i>(w, rk_load(row, voff, soff), acc);
+                soff = rk_advance(soff, dbytes);
+            });
+        }
+        if (want_max) {
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+                if (acc[i] > st.vmax) { st.vmax = acc[i]; st.targ = t0 + i * k.d; }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            acc[i] = lane_coef * rk_dsigmoid(acc[i], k.nl, k.ns);   // acc now holds q
+            st.qsum += acc[i];
+        }
+        for (int c = 0; c < k.nch; ++c) {
+            const __amdgpu_buffer_rsrc_t row =
+                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+            float g[LEN];
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) g[j] = 0.f;
+            uint32_t soff = 0;
+            rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                const float xv = rk_load(row, voff, soff);
+                soff = rk_advance(soff, dbytes);
+                rk_static_for<0, LEN>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+                    constexpr int o = i - j;
+                    if constexpr (o >= 0 && o < R) g[j] = fmaf(acc[o], xv, g[j]);
+                });
+            });
+            rk_bwd_deposit<LEN>(g, c, slots);
+        }
+    }
+}
+
+// LDS path of the backward pass (d < 8): the chunk's input range is staged once per
+// channel for the conv and once more for the weight gradient.
+template <int LEN, int D>
+__device__ __forceinline__ int rk_bwd_lds_bands(const KernelCtx &k, int rows, float coef, bool want_max, float *tile,
+                                                float *slots, BwdState &st)
+{
+    constexpr int R = kLdsRows;
+    const int nb = rows / R;
+    if (nb == 0) return 0;
+    constexpr int G = kThreads / D;
+    const int tid = static_cast<int>(threadIdx.x);
+    const int bl_raw = tid / D;
+    const int r = tid - bl_raw * D;
+    for (int band0 = 0; band0 < nb; band0 += G) {
+        const int gb = min(G, nb - band0);
+        const bool active = bl_raw < gb;
+        const int bl = active ? bl_raw : gb - 1;        // idle lanes redo the chunk's last band with weight 0
+        const float lane_coef = active ? coef : 0.f;
+        const float *mine = tile + bl * R * D + r;
+        const int nin = (gb * R + LEN - 1) * D;
+        const uint32_t chunk_bytes = static_cast<uint32_t>(band0 * R * D) * 4u;
+        float acc[R];
+#pragma unroll
+        for (int i = 0; i < R; ++i) acc[i] = 0.f;
+        for (int c = 0; c < k.nch; ++c) {
+            const __amdgpu_buffer_rsrc_t row =
+                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+            float w[LEN];
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
+            rk_stage_tile(row, chunk_bytes, nin, tile);
+            rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                rk_taps<LEN, R, i>(w, mine[i * D], acc);
+            });
+        }
+        {
+            const int t0 = ((band0 + bl) * R) * D + r;
+            if (want_max) {
+#pragma unroll
+                for (int i = 0; i < R; ++i) {
+                    if (acc[i] > st.vmax) { st.vmax = acc[i]; st.targ = t0 + i * D; }
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < R; ++i) {
+                acc[i] = lane_coef * rk_dsigmoid(acc[i], k.nl, k.ns);
+                st.qsum += acc[i];
+            }
+        }
+        for (int c = 0; c < k.nch; ++c) {
+            const __amdgpu_buffer_rsrc_t row =
+                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+            rk_stage_tile(row, chunk_bytes, nin, tile);
+            float g[LEN];
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) g[j] = 0.f;
+            rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                const float xv = mine[i * D];
+                rk_static_for<0, LEN>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+                    constexpr int o = i - j;
+                    if constexpr (o >= 0 && o < R) g[j] = fmaf(acc[o], xv, g[j]);
+                });
+            });
+            rk_bwd_deposit<LEN>(g, c, slots);
+        }
+    }
+    return nb * R;
+}
+
+template <int LEN, int D>
+__device__ __forceinline__ int rk_bwd_lds_dispatch(const KernelCtx &k, int rows, float coef, bool want_max,
+                                                   float *tile, float *slots, BwdState &st)
+{
+    if constexpr (D < kLdsMaxD) {
+        if (k.d == D) return rk_bwd_lds_bands<LEN, D>(k, rows, coef, want_max, tile, slots, st);
+        return rk_bwd_lds_dispatch<LEN, D + 1>(k, rows, coef, want_max, tile, slots, st);
+    } else {
+        return 0;
+    }
+}
+
+template <int LEN>
+__device__ __forceinline__ void rk_backward_body(const KernelCtx &k, int nout, float coef, bool want_max,
+                                                 float *tile, float *slots, BwdState &st)
+{
+    const int d = k.d;
+    const int total_rows = nout / d;
+    const int tail = nout - total_rows * d;
+    int row0 = 0;
+    if (d < kLdsMaxD) row0 = rk_bwd_lds_dispatch<LEN, 1>(k, total_rows, coef, want_max, tile, slots, st);
+    const int rows = total_rows - row0;   // rows left for the register path
+    const int nb32 = rows >> 5;
+    if (nb32) { rk_bwd_segment<LEN, 32>(k, row0, nb32, d, coef, want_max, slots, st); row0 += nb32 << 5; }
+    if (rows & 16) { rk_bwd_segment<LEN, 16>(k, row0, 1, d, coef, want_max, slots, st); row0 += 16; }
+    if (rows & 8) { rk_bwd_segment<LEN, 8>(k, row0, 1, d, coef, want_max, slots, st); row0 += 8; }
+    if (rows & 4) { rk_bwd_segment<LEN, 4>(k, row0, 1, d, coef, want_max, slots, st); row0 += 4; }
+    if (rows & 2) { rk_bwd_segment<LEN, 2>(k, row0, 1, d, coef, want_max, slots, st); row0 += 2; }
+    if (rows & 1) { rk_bwd_segment<LEN, 1>(k, row0, 1, d, coef, want_max, slots, st); row0 += 1; }
+    if (tail) rk_bwd_segment<LEN, 1>(k, row0, 1, tail, coef, want_max, slots, st);
+}
+
+// grid: B*K workgroups.  grad_out is B x (F*K); plane_soft / plane_max are the plane
+// indices of the softPPV and max features in it (plane_max < 0: max not included).
+// partial is B rows of (total_w + K) floats: weight gradients in the layout of
+// `weights`, then the K bias gradients.
+__global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict__ xpad, int row_len, int lead, int L, int C, int K,
+                                                        const RkKernelRec *__restrict__ recs,
+                                                        const int32_t *__restrict__ order,
+                                                        const int32_t *__restrict__ channels,
+                                                        const float *__restrict__ weights,
+                                                        const float *__restrict__ grad_out, int F, int plane_soft,
+                                                        int plane_max, float lambda, float nl, float ns,
+                                                        float *__restrict__ partial, int total_w)
+{
+    __shared__ float tile[kLdsTileWords];
+    __shared__ float slots[kBwdMaxTerms * kBwdSlots];
+    __shared__ float s_q[kWaves];
+    __shared__ float s_max[kWaves];
+    __shared__ int s_arg[kWaves];
+    const int b = blockIdx.x / K;
+    const int kid = order[blockIdx.x - b * K];
+    const RkKernelRec rec = recs[kid];
+    KernelCtx k = rk_make_ctx(rec, xpad, row_len, lead, L, C, b, channels, weights);
+    k.nl = nl;
+    k.ns = fmaf(rec.bias, nl, ns);
+
+    const int nterms = rec.nch * rec.len;
+    for (int i = threadIdx.x; i < nterms * kBwdSlots; i += kThreads) slots[i] = 0.f;
+    __syncthreads();
+
+    const float *g_row = grad_out + static_cast<size_t>(b) * F * K;
+    const float g_soft = g_row[static_cast<size_t>(plane_soft) * K + kid];
+    const float coef = g_soft * lambda / static_cast<float>(rec.nout);
+    const bool want_max = plane_max >= 0;
+
+    BwdState st;
+    st.qsum = 0.f;
+    st.vmax = -INFINITY;
+    st.targ = 0;
+    if (rec.len == 7) rk_backward_body<7>(k, rec.nout, coef, want_max, tile, slots, st);
+    else if (rec.len == 9) rk_backward_body<9>(k, rec.nout, coef, want_max, tile, slots, st);
+    else rk_backward_body<11>(k, rec.nout, coef, want_max, tile, slots, st);
+
+    // close the lane reductions: sum of q, and (max, first position) pairs
+    float qsum = st.qsum, vmax = st.vmax;
+    int targ = st.targ;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        qsum += __shfl_xor(qsum, off);
+        const float om = __shfl_xor(vmax, off);
+        const int ot = __shfl_xor(targ, off);
+        if (om > vmax || (om == vmax && ot < targ)) { vmax = om; targ = ot; }
+    }
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { s_q[wave] = qsum; s_max[wave] = vmax; s_arg[wave] = targ; }
+    __syncthreads();   // also orders the slot updates before the slot sums below
+    float gq = s_q[0], gm = s_max[0];
+    int ga = s_arg[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) {
+        gq += s_q[w];
+        if (s_max[w] > gm || (s_max[w] == gm && s_arg[w] < ga)) { gm = s_max[w]; ga = s_arg[w]; }
+    }
+    const float g_max = want_max ? g_row[static_cast<size_t>(plane_max) * K + kid] : 0.f;
+
+    float *prow = partial + static_cast<size_t>(b) * (static_cast<size_t>(total_w) + K);
+    const int t = static_cast<int>(threadIdx.x);
+    if (t < nterms) {
+        float sum = 0.f;
+#pragma unroll
+        for (int l = 0; l < kBwdSlots; ++l) sum += slots[t * kBwdSlots + l];
+        if (want_max) {
+            const int c = t / rec.len, j = t - c * rec.len;
+            const float *xrow = reinterpret_cast<const float *>(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes);
+            sum = fmaf(g_max, xrow[ga + j * rec.dil], sum);
+        }
+        prow[rec.w_off + t] = sum;
+    }
+    if (t == 0) prow[total_w + kid] = gq + g_max;
+}
+
+// out[i] = sum_b partial[b][i] for i < width, in ascending b; the first total_w
+// entries go to grad_w, the remaining K to grad_b.
+__global__ __launch_bounds__(256) void rk_reduce_batch(const float *__restrict__ partial, int B, int width, int total_w,
+                                                       float *__restrict__ grad_w, float *__restrict__ grad_b)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= width) return;
+    float sum = 0.f;
+    for (int b = 0; b < B; ++b) sum += partial[static_cast<size_t>(b) * width + i];
+    if (i < total_w) grad_w[i] = sum;
+    else grad_b[i - total_w] = sum;
+}
+
+// ------------------------------------------------------------------ launchers
+
+int rk_launch_backward(const rocket_kernels *h, const float *xpad, int32_t B, const float *grad_out, int F,
+                       int plane_soft, int plane_max, float lambda, float nl, float ns, float *partial,
+                       void *stream_ptr)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_ptr);
+    const int total_w = static_cast<int>(h->w_off[h->K]);
+    hipLaunchKernelGGL(rk_backward, dim3(static_cast<unsigned>(B) * h->K), dim3(kThreads), 0, stream, xpad,
+                       static_cast<int>(h->row_len), h->lead, h->L, h->C, h->K, h->d_rec, h->d_order, h->d_channels,
+                       h->d_weights, grad_out, F, plane_soft, plane_max, lambda, nl, ns, partial, total_w);
+    return hipGetLastError() == hipSuccess ? ROCKET_OK : ROCKET_EHIP;
+}
+
+int rk_launch_reduce_batch(const rocket_kernels *h, const float *partial, int32_t B, float *grad_w, float *grad_b,
+                           void *stream_ptr)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_ptr);
+    const int total_w = static_cast<int>(h->w_off[h->K]);
+    const int width = total_w + h->K;
+    hipLaunchKernelGGL(rk_reduce_batch, dim3((width + 255) / 256), dim3(256), 0, stream, partial, B, width, total_w,
+                       grad_w, grad_b);
+    return hipGetLastError() == hipSuccess ? ROCKET_OK : ROCKET_EHIP;
+}

@@ -1,0 +1,178 @@
+// Device-side helpers shared by the forward and backward translation units of the
+// ROCKET transform library (gfx950).  Strip decomposition, notation and the contract
+// of every entry point: include/rocket.h and the head of rocket_forward.hip.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <type_traits>
+
+#include "rocket_internal.hpp"
+
+#ifndef RK_RMAX
+#define RK_RMAX 32
+#endif
+#ifndef RK_WPE
+#define RK_WPE 6
+#endif
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr float kLog2e = 1.4426950408889634f;
+
+
+struct PoolState {
+    float vmax;   // per lane
+    float ssum;   // per lane
+    int cnt;      // wavefront-uniform: positives seen by this wavefront
+};
+
+// Raw buffer descriptor (stride 0, 32-bit data format) over `bytes` bytes at `base`.
+// Buffer loads take the address as descriptor base + scalar offset + lane offset,
+// so the walk along a strip costs scalar adds only; reads past `bytes` return 0.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rk_row_buffer(const char *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0, static_cast<int>(bytes), 0x00020000);
+}
+
+__device__ __forceinline__ float rk_load(__amdgpu_buffer_rsrc_t row, uint32_t lane_bytes, uint32_t uniform_bytes)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(row, static_cast<int>(lane_bytes),
+                                                                          static_cast<int>(uniform_bytes), 0));
+}
+
+// Advances a scalar byte offset by `step` and hides the result from the optimiser, so
+// the offsets of a strip's loads form one running scalar add per load instead of
+// dozens of precomputed multiples that would not fit the scalar register file
+// (they were spilled to vector lanes and read back once per channel).
+__device__ __forceinline__ uint32_t rk_advance(uint32_t off, uint32_t step)
+{
+    off += step;
+    asm volatile("" : "+s"(off));
+    return off;
+}
+
+// Compile-time loop: f(integral_constant<int, I>) for I in [I0, N).  Every index into
+// the per-lane accumulator and weight arrays below comes from such a constant, so the
+// arrays always live in named registers (a run-time index would make the compiler
+// address the register file indirectly).
+template <int I0, int N, class F>
+__device__ __forceinline__ void rk_static_for(F &&f)
+{
+    if constexpr (I0 < N) {
+        f(std::integral_constant<int, I0>{});
+        rk_static_for<I0 + 1, N>(f);
+    }
+}
+
+// Input value number I of a strip feeds every output it overlaps: acc[I-j] += w[j]*x_I.
+template <int LEN, int R, int I>
+__device__ __forceinline__ void rk_taps(const float (&w)[LEN], float xv, float (&acc)[R])
+{
+    rk_static_for<0, LEN>([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        constexpr int o = I - j;
+        if constexpr (o >= 0 && o < R) acc[o] = fmaf(w[j], xv, acc[o]);
+    });
+}
+
+// Pooling of R finished sums z = y - bias (section 3.2).  The bias is folded into
+// the pooling: max(y) = max(z) + bias (added once per kernel at the end),
+// y > 0 <=> z > -bias, and lambda*y + shift = lambda*z + (shift + lambda*bias).
+// `mask` is uniform; ns already contains the bias term.
+template <int R>
+__device__ __forceinline__ void rk_pool(const float (&acc)[R], uint32_t mask, float negbias, float nl, float ns,
+                                        PoolState &st)
+{
+    if (mask & ROCKET_F_MAX) {
+#pragma unroll
+        for (int i = 0; i < R; ++i) st.vmax = fmaxf(st.vmax, acc[i]);
+    }
+    if (mask & ROCKET_F_PPV) {   // Eq. 1-2: strict y > 0, counted per wavefront in a scalar register
+#pragma unroll
+        for (int i = 0; i < R; ++i) st.cnt += __builtin_popcountll(__ballot(acc[i] > negbias));
+    }
+    if (mask & ROCKET_F_SOFTPPV) {
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            // Eq. 3: 1/(1+exp(-(lambda*y+shift))) with nl = -lambda*log2(e), ns = -(shift+lambda*bias)*log2(e)
+            const float e = __builtin_amdgcn_exp2f(fmaf(acc[i], nl, ns));
+            st.ssum += __builtin_amdgcn_rcpf(1.f + e);
+        }
+    }
+}
+
+struct KernelCtx {
+    const char *xk;        // padded row of channel 0 of this series, shifted by -p (bytes)
+    size_t row_bytes;      // bytes per padded row
+    uint32_t span_bytes;   // bytes from xk to the end of its row
+    const int32_t *chans;  // this kernel's channel list
+    const float *wts;      // this kernel's weights, channel-major
+    int nch, d;
+    int pad, L;            // the kernel's padding and the series length
+    float negbias;         // -bias
+    uint32_t mask;
+    float nl, ns;          // softPPV: exp2(z*nl + ns) = exp(-(lambda*y + shift))
+};
+
+// LDS path for small dilations (d < kLdsMaxD).  With d < 64 the strips of a wavefront start
+// kLdsRows*d floats apart, so direct loads would touch a different cache line per
+// lane group.  Instead the workgroup copies the contiguous input range of a
+// chunk of bands into LDS with coalesced loads and the lanes read their strips
+// from there.  Bands have kLdsRows = 17 rows: an odd row count makes the stride
+// between neighbouring bands odd (times d), which spreads the strided LDS reads
+// over the banks without padding.  D is a template parameter so that the LDS
+// read offsets i*D*4 are immediates.
+#ifndef RK_LDS_ROWS
+#define RK_LDS_ROWS 17
+#endif
+#ifndef RK_LDS_MAXD
+#define RK_LDS_MAXD 16
+#endif
+constexpr int kFewMinD = 256;            // few-rows path needs at least a workgroup of columns
+constexpr int kLdsRows = RK_LDS_ROWS;
+constexpr int kLdsMaxD = RK_LDS_MAXD;                             // dilations below this take this path
+constexpr int kLdsStage = 4;                                      // staged words per lane per round
+constexpr int kLdsTileWords = ((kLdsRows * kThreads + 10 * (kLdsMaxD - 1)) / (kThreads * kLdsStage) + 1) * kThreads * kLdsStage;
+
+// Copies `nin` floats starting `chunk_bytes` into a row to the LDS tile with coalesced
+// loads (rounded up to whole rounds of kThreads*kLdsStage words: the tile and the
+// workspace slack are sized for that).  Barriers on both sides: nobody still reads the
+// previous contents, and the new contents are visible to all lanes afterwards.
+__device__ __forceinline__ void rk_stage_tile(__amdgpu_buffer_rsrc_t row, uint32_t chunk_bytes, int nin, float *tile)
+{
+    const int tid = static_cast<int>(threadIdx.x);
+    __syncthreads();
+    for (int base = 0; base < nin; base += kThreads * kLdsStage) {
+        float v[kLdsStage];
+#pragma unroll
+        for (int u = 0; u < kLdsStage; ++u)
+            v[u] = rk_load(row, static_cast<uint32_t>(tid + u * kThreads) * 4u,
+                           chunk_bytes + static_cast<uint32_t>(base) * 4u);
+#pragma unroll
+        for (int u = 0; u < kLdsStage; ++u) tile[base + tid + u * kThreads] = v[u];
+    }
+    __syncthreads();
+}
+
+
+// Fills the per-workgroup kernel context from the packed record of kernel `rec` and series b.
+__device__ __forceinline__ KernelCtx rk_make_ctx(const RkKernelRec &rec, const float *xpad, int row_len, int lead, int L,
+                                                 int C, int b, const int32_t *channels, const float *weights)
+{
+    KernelCtx k;
+    k.row_bytes = static_cast<size_t>(row_len) * 4;
+    k.xk = reinterpret_cast<const char *>(xpad) + static_cast<size_t>(b) * C * k.row_bytes +
+           static_cast<size_t>(lead - rec.pad) * 4;
+    k.span_bytes = static_cast<uint32_t>(row_len - (lead - rec.pad)) * 4u;
+    k.chans = channels + rec.ch_off;
+    k.wts = weights + rec.w_off;
+    k.nch = rec.nch;
+    k.d = rec.dil;
+    k.pad = rec.pad;
+    k.L = L;
+    k.negbias = -rec.bias;
+    k.mask = 0;
+    k.nl = 0.f;
+    k.ns = 0.f;
+    return k;
+}

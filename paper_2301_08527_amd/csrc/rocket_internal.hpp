@@ -1,4 +1,4 @@
-// Internal declarations shared by the host sampler and the HIP translation unit.
+// Internal declarations shared by the host sampler and the HIP translation units.
 #pragma once
 #include <cstdint>
 #include <string>
@@ -51,5 +51,15 @@ int rk_fail(int code, const std::string &msg);
 
 // sampler.cpp: fills the per-kernel arrays of `h` (K, C, L already set)
 void rk_sample_kernels(uint64_t seed, rocket_kernels &h);
-// plan.cpp part: offsets, launch order, padded row geometry; returns ROCKET_OK or an error
+// rocket_api.hip: offsets, launch order, padded row geometry; returns ROCKET_OK or an error
 int rk_finish_handle(rocket_kernels &h);
+
+// Kernel launchers (rocket_forward.hip, rocket_backward.hip).  `stream` is a hipStream_t.
+// They enqueue and return ROCKET_OK, or ROCKET_EHIP if the launch itself was rejected.
+int rk_launch_pad(const rocket_kernels *h, const float *x, int32_t B, float *xpad, void *stream);
+int rk_launch_forward(const rocket_kernels *h, const float *xpad, int32_t B, uint32_t mask, float nl, float ns,
+                      float *out, void *stream);
+int rk_launch_backward(const rocket_kernels *h, const float *xpad, int32_t B, const float *grad_out, int F,
+                       int plane_soft, int plane_max, float lambda, float nl, float ns, float *partial, void *stream);
+int rk_launch_reduce_batch(const rocket_kernels *h, const float *partial, int32_t B, float *grad_w, float *grad_b,
+                           void *stream);
