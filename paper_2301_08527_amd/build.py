@@ -14,12 +14,12 @@ COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-KERNEL_TUS = ("rocket_forward.hip", "rocket_backward.hip")   # translation units that hold device code
+KERNEL_TUS = ("rocket_forward.hip", "rocket_forward_short.hip", "rocket_backward.hip")   # translation units that hold device code
 HOST_TUS = ("rocket_api.hip",)
 
 
 def sources():
-    names = ("sampler.cpp", "rocket_internal.hpp", "rocket_device.hpp") + KERNEL_TUS + HOST_TUS
+    names = ("sampler.cpp", "rocket_internal.hpp", "rocket_device.hpp", "rocket_forward_impl.hpp") + KERNEL_TUS + HOST_TUS
     return [os.path.join(CSRC, f) for f in names] + [os.path.join(ROOT, "include", "rocket.h")]
 
 

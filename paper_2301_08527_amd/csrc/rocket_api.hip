@@ -339,6 +339,7 @@ static int ensure_device(rocket_kernels *h, hipStream_t stream)
 }
 
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kShortSeries = 8192;       // longest series handled by the one-wavefront forward kernel
 constexpr int kBwdMaxTerms = 9 * 11;     // the backward kernel holds at most 9 channels x 11 weights per kernel
 
 // ------------------------------------------------------------------ launches
@@ -375,8 +376,10 @@ extern "C" int rocket_transform(rocket_kernels *h, const float *x_dev, int32_t B
     const float nl = -lambda * kLog2e, ns = -shift * kLog2e;
     rc = profile_mark(h, stream, true);
     if (rc != ROCKET_OK) return rc;
-    if (rk_launch_forward(h, xpad, B, mask, nl, ns, out_dev, stream) != ROCKET_OK)
-        return rk_fail(ROCKET_EHIP, "launch of the forward kernel failed");
+    // series of at most kShortSeries samples: one wavefront per (series, kernel) instead of four
+    const int launched = h->L <= kShortSeries ? rk_launch_forward_short(h, xpad, B, mask, nl, ns, out_dev, stream)
+                                              : rk_launch_forward(h, xpad, B, mask, nl, ns, out_dev, stream);
+    if (launched != ROCKET_OK) return rk_fail(ROCKET_EHIP, "launch of the forward kernel failed");
     return profile_mark(h, stream, false);
 }
 

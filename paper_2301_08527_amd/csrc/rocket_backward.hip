@@ -161,7 +161,7 @@ __device__ __forceinline__ int rk_bwd_lds_bands(const KernelCtx &k, int rows, fl
             float w[LEN];
 #pragma unroll
             for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
-            rk_stage_tile(row, chunk_bytes, nin, tile);
+            rk_stage_tile<kThreads>(row, chunk_bytes, nin, tile);
             rk_static_for<0, R + LEN - 1>([&](auto ic) {
                 constexpr int i = decltype(ic)::value;
                 rk_taps<LEN, R, i>(w, mine[i * D], acc);
@@ -184,7 +184,7 @@ __device__ __forceinline__ int rk_bwd_lds_bands(const KernelCtx &k, int rows, fl
         for (int c = 0; c < k.nch; ++c) {
             const __amdgpu_buffer_rsrc_t row =
                 rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
-            rk_stage_tile(row, chunk_bytes, nin, tile);
+            rk_stage_tile<kThreads>(row, chunk_bytes, nin, tile);
             float g[LEN];
 #pragma unroll
             for (int j = 0; j < LEN; ++j) g[j] = 0.f;

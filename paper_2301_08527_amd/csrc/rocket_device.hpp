@@ -132,24 +132,28 @@ constexpr int kFewMinD = 256;            // few-rows path needs at least a workg
 constexpr int kLdsRows = RK_LDS_ROWS;
 constexpr int kLdsMaxD = RK_LDS_MAXD;                             // dilations below this take this path
 constexpr int kLdsStage = 4;                                      // staged words per lane per round
-constexpr int kLdsTileWords = ((kLdsRows * kThreads + 10 * (kLdsMaxD - 1)) / (kThreads * kLdsStage) + 1) * kThreads * kLdsStage;
+// words of the LDS tile of a workgroup of NT lanes: the largest chunk (NT strips of kLdsRows rows
+// plus the halo of the widest kernel at the largest LDS-path dilation), rounded up to whole staging rounds
+constexpr int rk_tile_words(int nt) { return ((kLdsRows * nt + 10 * (kLdsMaxD - 1)) / (nt * kLdsStage) + 1) * nt * kLdsStage; }
+constexpr int kLdsTileWords = rk_tile_words(kThreads);
 
 // Copies `nin` floats starting `chunk_bytes` into a row to the LDS tile with coalesced
-// loads (rounded up to whole rounds of kThreads*kLdsStage words: the tile and the
+// loads (rounded up to whole rounds of NT*kLdsStage words: the tile and the
 // workspace slack are sized for that).  Barriers on both sides: nobody still reads the
 // previous contents, and the new contents are visible to all lanes afterwards.
+template <int NT>
 __device__ __forceinline__ void rk_stage_tile(__amdgpu_buffer_rsrc_t row, uint32_t chunk_bytes, int nin, float *tile)
 {
     const int tid = static_cast<int>(threadIdx.x);
     __syncthreads();
-    for (int base = 0; base < nin; base += kThreads * kLdsStage) {
+    for (int base = 0; base < nin; base += NT * kLdsStage) {
         float v[kLdsStage];
 #pragma unroll
         for (int u = 0; u < kLdsStage; ++u)
-            v[u] = rk_load(row, static_cast<uint32_t>(tid + u * kThreads) * 4u,
+            v[u] = rk_load(row, static_cast<uint32_t>(tid + u * NT) * 4u,
                            chunk_bytes + static_cast<uint32_t>(base) * 4u);
 #pragma unroll
-        for (int u = 0; u < kLdsStage; ++u) tile[base + tid + u * kThreads] = v[u];
+        for (int u = 0; u < kLdsStage; ++u) tile[base + tid + u * NT] = v[u];
     }
     __syncthreads();
 }

@@ -59,6 +59,9 @@ int rk_finish_handle(rocket_kernels &h);
 int rk_launch_pad(const rocket_kernels *h, const float *x, int32_t B, float *xpad, void *stream);
 int rk_launch_forward(const rocket_kernels *h, const float *xpad, int32_t B, uint32_t mask, float nl, float ns,
                       float *out, void *stream);
+// same kernel with one wavefront per (series, kernel), for short series
+int rk_launch_forward_short(const rocket_kernels *h, const float *xpad, int32_t B, uint32_t mask, float nl, float ns,
+                            float *out, void *stream);
 int rk_launch_backward(const rocket_kernels *h, const float *xpad, int32_t B, const float *grad_out, int F,
                        int plane_soft, int plane_max, float lambda, float nl, float ns, float *partial, void *stream);
 int rk_launch_reduce_batch(const rocket_kernels *h, const float *partial, int32_t B, float *grad_w, float *grad_b,
