@@ -89,9 +89,12 @@ def test_lambda_and_shift_sweep(lam, shift):
 
 
 @pytest.mark.parametrize("B,C,L,K", [(1, 1, 11, 40), (3, 2, 12, 40), (2, 9, 64, 100), (1, 20, 257, 150),
-                                     (2, 3, 1025, 120), (1, 12, 4099, 120)])
+                                     (2, 3, 1025, 120), (1, 12, 4099, 120), (2, 2, 8192, 100), (2, 2, 8193, 100),
+                                     (1, 5, 12289, 160), (1, 3, 20011, 160)])
 def test_small_and_ragged_shapes(B, C, L, K):
-    """shortest legal series, lengths that are not multiples of any tile, one series"""
+    """shortest legal series, lengths that are not multiples of any tile, one series;
+    lengths on both sides of the switch between the one-wavefront kernel (L <= 8192)
+    and the four-wavefront kernel"""
     rng = np.random.default_rng(L)
     x = rng.standard_normal((B, C, L)).astype(np.float32)
     h = rocket.rocket_make_kernels(7, K, C, L)
@@ -100,15 +103,17 @@ def test_small_and_ragged_shapes(B, C, L, K):
     check_forward(x, kr, out, 7)
 
 
-def test_imported_extreme_kernels():
+@pytest.mark.parametrize("L", [2000, 9000])
+def test_imported_extreme_kernels(L):
     """hand-built kernels: every length at d=1 and at the largest dilation,
-    padded and not, single output position, nine channels"""
+    padded and not, single output position, nine channels; once per forward kernel"""
     rng = np.random.default_rng(5)
-    C, L, B = 9, 2000, 3
+    C, B = 9, 3
     specs = []
     for ln in (7, 9, 11):
         dmax = (L - 1) // (ln - 1)
-        for d in (1, 2, 3, 17, 63, 64, 65, 100, dmax - 1, dmax):
+        for d in sorted({d for d in (1, 2, 3, 7, 8, 15, 16, 17, 63, 64, 65, 100, 255, 256, 257, dmax // 3, dmax - 1, dmax)
+                         if 1 <= d <= dmax}):
             for padded in (False, True):
                 nch = int(rng.integers(1, 10))
                 specs.append((ln, d, padded, nch))
@@ -161,6 +166,28 @@ def test_outputs_are_overwritten_and_repeatable():
         out2 = rocket.rocket_transform(h, xd, 3, workspace=ws, stream=s)
     s.synchronize()
     assert np.array_equal(a, out2.cpu().numpy())
+
+
+def test_more_than_nine_channels_forward_only():
+    """imported kernels may list more than nine channels: the forward pass takes them,
+    the backward pass rejects them with ROCKET_ESHAPE"""
+    import torch
+    rng = np.random.default_rng(6)
+    C, L, B, K = 14, 9001, 2, 24
+    length = rng.choice([7, 9, 11], K).astype(np.int32)
+    dil = rng.integers(1, 200, K).astype(np.int32)
+    pad = np.where(rng.integers(0, 2, K) == 1, (length - 1) * dil // 2, 0).astype(np.int32)
+    nch = rng.integers(10, C + 1, K).astype(np.int32)
+    chans = np.concatenate([rng.permutation(C)[:m] for m in nch]).astype(np.int32)
+    w = rng.standard_normal(int((nch * length).sum())).astype(np.float32)
+    bias = rng.uniform(-1, 1, K).astype(np.float32)
+    h = rocket.rocket_kernels_import(K, C, L, length, dil, pad, bias, nch, chans, w)
+    kr = rocket.rocket_kernels_view_get(h)
+    x = rng.standard_normal((B, C, L)).astype(np.float32)
+    check_forward(x, kr, _run(h, x, 7), 7)
+    with pytest.raises(rocket.RocketError) as e:
+        rocket.rocket_soft_ppv_backward(h, _gpu(x), 4, torch.zeros(B, K, device="cuda"))
+    assert e.value.code == rocket.ROCKET_ESHAPE
 
 
 def test_shape_mismatch_is_an_error():
