@@ -108,8 +108,9 @@ int32_t rocket_num_features(uint32_t feature_mask);
  * Bytes of device workspace that rocket_transform (backward = 0) or
  * rocket_soft_ppv_backward (backward = 1) needs for a batch of B series.
  * Returns 0 on invalid arguments.  The workspace holds a zero-padded copy of
- * the batch (so that dilated reads never leave a row) and, for the backward
- * pass, per-series partial gradients.  Its contents are scratch.
+ * the batch (so that dilated reads never leave a row) and partial results: for
+ * the transform the pooled values of every (series, time tile of a kernel), for
+ * the backward pass per-series partial gradients.  Its contents are scratch.
  */
 size_t rocket_workspace_bytes(const rocket_kernels *kernels, int32_t B, uint32_t feature_mask, int backward);
 

@@ -83,6 +83,63 @@ int rk_finish_handle(rocket_kernels &h)
     for (int32_t k = 0; k < K; ++k) h.order[k] = k;
     std::stable_sort(h.order.begin(), h.order.end(),
                      [&](int32_t a, int32_t b) { return cost[a] > cost[b]; });
+    // Forward jobs.  A kernel's rows are cut into tiles of at least kTilePositions output
+    // positions (whole LDS chunks or whole 32-row bands); jobs are ordered by the time
+    // window they start in, so the workgroups that run together read one stretch of the
+    // series and an XCD's live set stays within its L2.  Kernels whose single tile spans
+    // most of the series (large dilations) come last.
+    {
+        struct Key { int64_t window; double cost; };
+        std::vector<Key> keys;
+        h.jobs.clear();
+        h.kjob_off.assign(K + 1, 0);
+        std::vector<std::vector<int32_t>> per_kernel(K);
+        for (int32_t k = 0; k < K; ++k) {
+            const int64_t d = h.dilation[k];
+            const int64_t n = static_cast<int64_t>(h.L) + 2LL * h.padding[k] - static_cast<int64_t>(h.length[k] - 1) * d;
+            const int64_t rows = n / d, tail = n - rows * d;
+            const double per_pos = static_cast<double>(h.n_ch[k]) * h.length[k];
+            auto add = [&](int64_t r0, int64_t r1, int flags, int64_t window) {
+                RkJob j;
+                j.kernel = k; j.row0 = static_cast<int32_t>(r0); j.row1 = static_cast<int32_t>(r1); j.flags = flags;
+                per_kernel[k].push_back(static_cast<int32_t>(h.jobs.size()));
+                h.jobs.push_back(j);
+                const double pos = static_cast<double>((r1 - r0) * d + ((flags & 1) ? tail : 0));
+                keys.push_back({window, pos * per_pos});
+            };
+            const int64_t unit = d < kLdsMaxD ? kLdsRows * (kThreads / d) : 32;     // rows per LDS chunk / tallest band
+            const int64_t per_tile = unit * std::max<int64_t>(1, (kTilePositions + unit * d - 1) / (unit * d));
+            const int64_t tiles = std::max<int64_t>(1, rows / per_tile);
+            const bool few = d >= kFewMinD && rows + (tail > 0 ? 1 : 0) <= kFewRowsMax;
+            if (few || tiles == 1) {
+                // one job; a tile that reaches over more than two windows counts as "everywhere"
+                const bool wide = (rows + h.length[k]) * d > 2 * kTilePositions;
+                add(0, rows, 3, wide ? INT64_MAX : 0);
+            } else {
+                for (int64_t t = 0; t < tiles; ++t) {
+                    const int64_t r0 = t * per_tile, r1 = (t == tiles - 1) ? rows : (t + 1) * per_tile;
+                    add(r0, r1, (t == tiles - 1) ? 1 : 0, (r0 * d) / kTilePositions);
+                }
+            }
+        }
+        const size_t J = h.jobs.size();
+        if (J > static_cast<size_t>(INT32_MAX)) return rk_fail(ROCKET_EINVAL, "too many forward jobs");
+        std::vector<int32_t> perm(J);
+        for (size_t i = 0; i < J; ++i) perm[i] = static_cast<int32_t>(i);
+        std::stable_sort(perm.begin(), perm.end(), [&](int32_t a, int32_t b) {
+            if (keys[a].window != keys[b].window) return keys[a].window < keys[b].window;
+            return keys[a].cost > keys[b].cost;
+        });
+        std::vector<RkJob> sorted(J);
+        std::vector<int32_t> where(J);
+        for (size_t i = 0; i < J; ++i) { sorted[i] = h.jobs[perm[i]]; where[perm[i]] = static_cast<int32_t>(i); }
+        h.jobs.swap(sorted);
+        h.kjob_idx.clear();
+        for (int32_t k = 0; k < K; ++k) {
+            for (int32_t j : per_kernel[k]) h.kjob_idx.push_back(where[j]);
+            h.kjob_off[k + 1] = static_cast<int32_t>(h.kjob_idx.size());
+        }
+    }
     // padded rows: `lead` zeros, the L samples, then zeros: at least the largest padding,
     // and at least the largest dilation (idle lanes of a partial last row read up to one
     // row of d floats past the series)
@@ -285,12 +342,15 @@ static size_t padded_batch_bytes(const rocket_kernels *h, int32_t B)
 
 static size_t backward_partial_floats(const rocket_kernels *h) { return static_cast<size_t>(h->w_off[h->K]) + h->K; }
 
+// forward: three words (max, positive count, sigmoid sum) per (series, job)
+static size_t forward_partial_floats(const rocket_kernels *h) { return 3 * h->jobs.size(); }
+
 extern "C" size_t rocket_workspace_bytes(const rocket_kernels *h, int32_t B, uint32_t mask, int backward)
 {
     if (!h || B < 1 || rocket_num_features(mask) == 0) return 0;
     size_t bytes = padded_batch_bytes(h, B);
-    if (backward) bytes += static_cast<size_t>(B) * backward_partial_floats(h) * 4;
-    return bytes;
+    bytes += static_cast<size_t>(B) * (backward ? backward_partial_floats(h) : forward_partial_floats(h)) * 4;
+    return static_cast<size_t>(round_up(static_cast<int64_t>(bytes), 256));
 }
 
 // ------------------------------------------------------------------ device mirror
@@ -304,10 +364,13 @@ static int ensure_device(rocket_kernels *h, hipStream_t stream)
     const size_t ord_b = round_up(static_cast<int64_t>(K) * 4, 256);
     const size_t ch_b = round_up(static_cast<int64_t>(h->channels.size()) * 4, 256);
     const size_t w_b = round_up(static_cast<int64_t>(h->weights.size()) * 4, 256);
+    const size_t job_b = round_up(static_cast<int64_t>(h->jobs.size()) * sizeof(RkJob), 256);
+    const size_t koff_b = round_up(static_cast<int64_t>(K + 1) * 4, 256);
+    const size_t kidx_b = round_up(static_cast<int64_t>(h->kjob_idx.size()) * 4, 256);
     if (h->d_blob && h->device != cur)
         return rk_fail(ROCKET_EINVAL, "handle was first used on another device");
     if (!h->d_blob) {
-        h->blob_bytes = rec_b + ord_b + ch_b + w_b;
+        h->blob_bytes = rec_b + ord_b + ch_b + w_b + job_b + koff_b + kidx_b;
         RK_HIP(hipMalloc(&h->d_blob, h->blob_bytes));
         h->device = cur;
         char *base = static_cast<char *>(h->d_blob);
@@ -315,6 +378,9 @@ static int ensure_device(rocket_kernels *h, hipStream_t stream)
         h->d_order = reinterpret_cast<const int32_t *>(base + rec_b);
         h->d_channels = reinterpret_cast<const int32_t *>(base + rec_b + ord_b);
         h->d_weights = reinterpret_cast<float *>(base + rec_b + ord_b + ch_b);
+        h->d_jobs = reinterpret_cast<const RkJob *>(base + rec_b + ord_b + ch_b + w_b);
+        h->d_kjob_off = reinterpret_cast<const int32_t *>(base + rec_b + ord_b + ch_b + w_b + job_b);
+        h->d_kjob_idx = reinterpret_cast<const int32_t *>(base + rec_b + ord_b + ch_b + w_b + job_b + koff_b);
         h->params_dirty = true;
     }
     if (h->params_dirty) {
@@ -332,6 +398,9 @@ static int ensure_device(rocket_kernels *h, hipStream_t stream)
         RK_HIP(hipMemcpyAsync(const_cast<int32_t *>(h->d_order), h->order.data(), K * 4, hipMemcpyHostToDevice, stream));
         RK_HIP(hipMemcpyAsync(const_cast<int32_t *>(h->d_channels), h->channels.data(), h->channels.size() * 4, hipMemcpyHostToDevice, stream));
         RK_HIP(hipMemcpyAsync(h->d_weights, h->weights.data(), h->weights.size() * 4, hipMemcpyHostToDevice, stream));
+        RK_HIP(hipMemcpyAsync(const_cast<RkJob *>(h->d_jobs), h->jobs.data(), h->jobs.size() * sizeof(RkJob), hipMemcpyHostToDevice, stream));
+        RK_HIP(hipMemcpyAsync(const_cast<int32_t *>(h->d_kjob_off), h->kjob_off.data(), (K + 1) * 4, hipMemcpyHostToDevice, stream));
+        RK_HIP(hipMemcpyAsync(const_cast<int32_t *>(h->d_kjob_idx), h->kjob_idx.data(), h->kjob_idx.size() * 4, hipMemcpyHostToDevice, stream));
         RK_HIP(hipStreamSynchronize(stream));
         h->params_dirty = false;
     }
@@ -353,7 +422,8 @@ static int check_common(const char *fn, const rocket_kernels *h, const void *x, 
     if (B < 1) return rk_fail(ROCKET_EINVAL, who + ": B must be >= 1");
     if (rocket_num_features(mask) == 0) return rk_fail(ROCKET_EINVAL, who + ": feature mask must be a non-empty subset of 7");
     if (!std::isfinite(lambda) || !std::isfinite(shift)) return rk_fail(ROCKET_EINVAL, who + ": lambda and shift must be finite");
-    if (static_cast<int64_t>(B) * h->K > INT32_MAX) return rk_fail(ROCKET_EINVAL, who + ": B*K exceeds the grid limit");
+    if (static_cast<int64_t>(B) * static_cast<int64_t>(std::max<size_t>(h->jobs.size(), h->K)) > INT32_MAX)
+        return rk_fail(ROCKET_EINVAL, who + ": B times the number of work items exceeds the grid limit");
     const size_t need = rocket_workspace_bytes(h, B, mask, backward);
     if (!ws || ws_bytes < need)
         return rk_fail(ROCKET_EWORKSPACE, who + ": workspace of " + std::to_string(need) + " bytes required");
@@ -377,10 +447,15 @@ extern "C" int rocket_transform(rocket_kernels *h, const float *x_dev, int32_t B
     rc = profile_mark(h, stream, true);
     if (rc != ROCKET_OK) return rc;
     // series of at most kShortSeries samples: one wavefront per (series, kernel) instead of four
-    const int launched = h->L <= kShortSeries ? rk_launch_forward_short(h, xpad, B, mask, nl, ns, out_dev, stream)
-                                              : rk_launch_forward(h, xpad, B, mask, nl, ns, out_dev, stream);
+    float *partials = reinterpret_cast<float *>(static_cast<char *>(ws) + padded_batch_bytes(h, B));
+    const int launched = h->L <= kShortSeries ? rk_launch_forward_short(h, xpad, B, mask, nl, ns, partials, stream)
+                                              : rk_launch_forward(h, xpad, B, mask, nl, ns, partials, stream);
     if (launched != ROCKET_OK) return rk_fail(ROCKET_EHIP, "launch of the forward kernel failed");
-    return profile_mark(h, stream, false);
+    rc = profile_mark(h, stream, false);
+    if (rc != ROCKET_OK) return rc;
+    if (rk_launch_finalize(h, partials, B, mask, out_dev, stream) != ROCKET_OK)
+        return rk_fail(ROCKET_EHIP, "launch of the feature kernel failed");
+    return ROCKET_OK;
 }
 
 extern "C" int rocket_soft_ppv_backward(rocket_kernels *h, const float *x_dev, int32_t B, uint32_t mask,

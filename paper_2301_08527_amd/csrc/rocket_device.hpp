@@ -15,7 +15,6 @@
 #ifndef RK_WPE
 #define RK_WPE 6
 #endif
-constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -122,15 +121,6 @@ struct KernelCtx {
 // between neighbouring bands odd (times d), which spreads the strided LDS reads
 // over the banks without padding.  D is a template parameter so that the LDS
 // read offsets i*D*4 are immediates.
-#ifndef RK_LDS_ROWS
-#define RK_LDS_ROWS 17
-#endif
-#ifndef RK_LDS_MAXD
-#define RK_LDS_MAXD 16
-#endif
-constexpr int kFewMinD = 256;            // few-rows path needs at least a workgroup of columns
-constexpr int kLdsRows = RK_LDS_ROWS;
-constexpr int kLdsMaxD = RK_LDS_MAXD;                             // dilations below this take this path
 constexpr int kLdsStage = 4;                                      // staged words per lane per round
 // words of the LDS tile of a workgroup of NT lanes: the largest chunk (NT strips of kLdsRows rows
 // plus the halo of the widest kernel at the largest LDS-path dilation), rounded up to whole staging rounds

@@ -51,11 +51,52 @@ int rk_launch_pad(const rocket_kernels *h, const float *x, int32_t B, float *xpa
 }
 
 int rk_launch_forward(const rocket_kernels *h, const float *xpad, int32_t B, uint32_t mask, float nl, float ns,
-                      float *out, void *stream_ptr)
+                      float *partials, void *stream_ptr)
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_ptr);
-    hipLaunchKernelGGL(rk_forward<kThreads>, dim3(static_cast<unsigned>(B) * h->K), dim3(kThreads), 0, stream, xpad,
-                       static_cast<int>(h->row_len), h->lead, h->L, h->C, h->K, h->d_rec, h->d_order, h->d_channels,
-                       h->d_weights, mask, nl, ns, out);
+    const int J = static_cast<int>(h->jobs.size());
+    hipLaunchKernelGGL(rk_forward<kThreads>, dim3(static_cast<unsigned>(B) * J), dim3(kThreads), 0, stream, xpad,
+                       static_cast<int>(h->row_len), h->lead, h->L, h->C, J, h->d_rec, h->d_jobs, h->d_channels,
+                       h->d_weights, mask, nl, ns, partials, B);
+    return hipGetLastError() == hipSuccess ? ROCKET_OK : ROCKET_EHIP;
+}
+
+// One thread per (series, kernel): combines the kernel's job partials in job order and
+// writes the feature planes out[b*F*K + f*K + k] (max + bias, count / n, sum / n).
+__global__ __launch_bounds__(256) void rk_finalize(const float *__restrict__ partials, int B, int K, int J,
+                                                   const RkKernelRec *__restrict__ recs,
+                                                   const int32_t *__restrict__ kjob_off,
+                                                   const int32_t *__restrict__ kjob_idx, uint32_t mask,
+                                                   float *__restrict__ out)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= B * K) return;
+    const int b = i / K, kid = i - b * K;
+    const size_t plane = static_cast<size_t>(B) * J;
+    const size_t base = static_cast<size_t>(b) * J;
+    float m = -INFINITY, sm = 0.f;
+    int cn = 0;
+    for (int q = kjob_off[kid]; q < kjob_off[kid + 1]; ++q) {
+        const size_t slot = base + kjob_idx[q];
+        m = fmaxf(m, partials[slot]);
+        cn += reinterpret_cast<const int *>(partials)[plane + slot];
+        sm += partials[2 * plane + slot];
+    }
+    const RkKernelRec rec = recs[kid];
+    const int F = __builtin_popcount(mask);
+    float *o = out + static_cast<size_t>(b) * F * K + kid;
+    int f = 0;
+    if (mask & ROCKET_F_MAX) { o[static_cast<size_t>(f) * K] = m + rec.bias; ++f; }
+    if (mask & ROCKET_F_PPV) { o[static_cast<size_t>(f) * K] = static_cast<float>(static_cast<double>(cn) / static_cast<double>(rec.nout)); ++f; }
+    if (mask & ROCKET_F_SOFTPPV) { o[static_cast<size_t>(f) * K] = sm / static_cast<float>(rec.nout); ++f; }
+}
+
+int rk_launch_finalize(const rocket_kernels *h, const float *partials, int32_t B, uint32_t mask, float *out,
+                       void *stream_ptr)
+{
+    hipStream_t stream = static_cast<hipStream_t>(stream_ptr);
+    const int total = B * h->K;
+    hipLaunchKernelGGL(rk_finalize, dim3((total + 255) / 256), dim3(256), 0, stream, partials, B, h->K,
+                       static_cast<int>(h->jobs.size()), h->d_rec, h->d_kjob_off, h->d_kjob_idx, mask, out);
     return hipGetLastError() == hipSuccess ? ROCKET_OK : ROCKET_EHIP;
 }

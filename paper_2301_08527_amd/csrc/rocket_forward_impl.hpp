@@ -41,11 +41,11 @@ __device__ __forceinline__ void rk_segment(const KernelCtx &k, int row0, int nba
 }
 
 template <int LEN, int D, int NT>
-__device__ __forceinline__ int rk_lds_bands(const KernelCtx &k, int rows, float *tile, PoolState &st)
+__device__ __forceinline__ int rk_lds_bands(const KernelCtx &k, int first_row, int end_row, float *tile, PoolState &st)
 {
     constexpr int R = kLdsRows;
-    const int nb = rows / R;
-    if (nb == 0) return 0;
+    const int nb = (end_row - first_row) / R;    // whole bands in [first_row, end_row)
+    if (nb == 0) return first_row;
     constexpr int G = NT / D;                 // bands per chunk
     const int tid = static_cast<int>(threadIdx.x);
     const int bl = tid / D;                         // lane's band inside the chunk
@@ -55,7 +55,7 @@ __device__ __forceinline__ int rk_lds_bands(const KernelCtx &k, int rows, float 
         const int gb = min(G, nb - band0);
         const bool active = bl < gb;
         const int nin = (gb * R + LEN - 1) * D;     // input floats of this chunk
-        const uint32_t chunk_bytes = static_cast<uint32_t>(band0 * R * D) * 4u;
+        const uint32_t chunk_bytes = static_cast<uint32_t>((first_row + band0 * R) * D) * 4u;
         float acc[R];
         auto channel = [&](int c) {
             const __amdgpu_buffer_rsrc_t row =
@@ -76,7 +76,7 @@ __device__ __forceinline__ int rk_lds_bands(const KernelCtx &k, int rows, float 
         for (int c = 0; c < k.nch; ++c) channel(c);
         if (active) rk_pool<R>(acc, k.mask, k.negbias, k.nl, k.ns, st);
     }
-    return nb * R;
+    return first_row + nb * R;
 }
 
 // Pooling of one finished sum (see rk_pool).
@@ -160,35 +160,35 @@ __device__ __forceinline__ void rk_few_rows(const KernelCtx &k, int rows, int ta
 
 // Calls rk_lds_bands<LEN, D> for the D that equals the kernel's dilation (D < kLdsMaxD).
 template <int LEN, int D, int NT>
-__device__ __forceinline__ int rk_lds_dispatch(const KernelCtx &k, int rows, float *tile, PoolState &st)
+__device__ __forceinline__ int rk_lds_dispatch(const KernelCtx &k, int first_row, int end_row, float *tile, PoolState &st)
 {
     if constexpr (D < kLdsMaxD) {
-        if (k.d == D) return rk_lds_bands<LEN, D, NT>(k, rows, tile, st);
-        return rk_lds_dispatch<LEN, D + 1, NT>(k, rows, tile, st);
+        if (k.d == D) return rk_lds_bands<LEN, D, NT>(k, first_row, end_row, tile, st);
+        return rk_lds_dispatch<LEN, D + 1, NT>(k, first_row, end_row, tile, st);
     } else {
-        return 0;
+        return first_row;
     }
 }
 
 template <int LEN, int NT>
-__device__ __forceinline__ void rk_forward_body(const KernelCtx &k, int nout, float *tile, PoolState &st)
+__device__ __forceinline__ void rk_forward_body(const KernelCtx &k, int nout, const RkJob job, float *tile, PoolState &st)
 {
     const int d = k.d;
     const int rows = nout / d;            // full rows of d outputs
     const int tail = nout - rows * d;     // outputs of the partial last row
-    int row0 = 0;
     // every branch below is uniform per workgroup
-    if (d >= kFewMinD) {
+    if ((job.flags & 2) && d >= kFewMinD) {
         const int nrows = rows + (tail > 0 ? 1 : 0);
         if (nrows <= 8) { rk_few_rows<LEN, 8, NT>(k, rows, tail, st); return; }
         if (nrows <= 16) { rk_few_rows<LEN, 16, NT>(k, rows, tail, st); return; }
-        if (nrows <= 24) { rk_few_rows<LEN, 24, NT>(k, rows, tail, st); return; }
+        if (nrows <= kFewRowsMax) { rk_few_rows<LEN, 24, NT>(k, rows, tail, st); return; }
     }
-    if (d < kLdsMaxD) row0 = rk_lds_dispatch<LEN, 1, NT>(k, rows, tile, st);
+    int row0 = job.row0;
+    if (d < kLdsMaxD) row0 = rk_lds_dispatch<LEN, 1, NT>(k, row0, job.row1, tile, st);
     // Register path for the remaining rows: bands of 32, 16, 8, 4, 2 rows, tallest first.
     // A band height is used when its strips fill the workgroup (bands x d >= NT); rows
     // that are left go to the next smaller height, and single rows take the rest.
-    int left = rows - row0;
+    int left = job.row1 - row0;
     auto bands_of = [&](auto rc, bool force) {
         constexpr int R = decltype(rc)::value;
         const int nb = left / R;
@@ -206,25 +206,28 @@ __device__ __forceinline__ void rk_forward_body(const KernelCtx &k, int nout, fl
     bands_of(std::integral_constant<int, 4>{}, false);
     bands_of(std::integral_constant<int, 2>{}, false);
     bands_of(std::integral_constant<int, 1>{}, true);
-    if (tail) rk_segment<LEN, 1, NT>(k, row0, 1, tail, st);
+    if ((job.flags & 1) && tail) rk_segment<LEN, 1, NT>(k, rows, 1, tail, st);
 }
 
-// grid: B*K workgroups; workgroup g handles series g / K and kernel order[g % K].
+// grid: B*J workgroups; workgroup g handles series g / J and job g % J (a row range of
+// one kernel).  It writes the job's partial pooling results: partials holds three planes
+// of B*J words (max of y - bias, count of y > 0, sum of sigmoids).
 template <int NT>
 #if RK_WPE
 __attribute__((amdgpu_waves_per_eu(RK_WPE)))
 #endif
-__global__ __launch_bounds__(NT) void rk_forward(const float *__restrict__ xpad, int row_len, int lead, int L, int C, int K,
+__global__ __launch_bounds__(NT) void rk_forward(const float *__restrict__ xpad, int row_len, int lead, int L, int C, int J,
                                                        const RkKernelRec *__restrict__ recs,
-                                                       const int32_t *__restrict__ order,
+                                                       const RkJob *__restrict__ jobs,
                                                        const int32_t *__restrict__ channels,
                                                        const float *__restrict__ weights, uint32_t mask, float nl,
-                                                       float ns, float *__restrict__ out)
+                                                       float ns, float *__restrict__ partials, int B)
 {
     __shared__ float tile[rk_tile_words(NT)];
-    const int b = blockIdx.x / K;
-    const int kid = order[blockIdx.x - b * K];
-    const RkKernelRec rec = recs[kid];
+    const int b = blockIdx.x / J;
+    const int jid = blockIdx.x - b * J;
+    const RkJob job = jobs[jid];
+    const RkKernelRec rec = recs[job.kernel];
     KernelCtx k = rk_make_ctx(rec, xpad, row_len, lead, L, C, b, channels, weights);
     k.mask = mask;
     k.nl = nl;
@@ -234,9 +237,9 @@ __global__ __launch_bounds__(NT) void rk_forward(const float *__restrict__ xpad,
     st.vmax = -INFINITY;
     st.ssum = 0.f;
     st.cnt = 0;
-    if (rec.len == 7) rk_forward_body<7, NT>(k, rec.nout, tile, st);
-    else if (rec.len == 9) rk_forward_body<9, NT>(k, rec.nout, tile, st);
-    else rk_forward_body<11, NT>(k, rec.nout, tile, st);
+    if (rec.len == 7) rk_forward_body<7, NT>(k, rec.nout, job, tile, st);
+    else if (rec.len == 9) rk_forward_body<9, NT>(k, rec.nout, job, tile, st);
+    else rk_forward_body<11, NT>(k, rec.nout, job, tile, st);
 
     // close the reductions: lanes -> wavefront (shuffles) -> workgroup (LDS)
     float vmax = st.vmax, ssum = st.ssum;
@@ -256,12 +259,10 @@ __global__ __launch_bounds__(NT) void rk_forward(const float *__restrict__ xpad,
         int cn = s_cnt[0];
 #pragma unroll
         for (int w = 1; w < (NT / 64); ++w) { m = fmaxf(m, s_max[w]); sm += s_sum[w]; cn += s_cnt[w]; }
-        const int F = __builtin_popcount(mask);
-        float *o = out + static_cast<size_t>(b) * F * K + kid;
-        int f = 0;
-        if (mask & ROCKET_F_MAX) { o[static_cast<size_t>(f) * K] = m + rec.bias; ++f; }
-        if (mask & ROCKET_F_PPV) { o[static_cast<size_t>(f) * K] = static_cast<float>(static_cast<double>(cn) / static_cast<double>(rec.nout)); ++f; }
-        if (mask & ROCKET_F_SOFTPPV) { o[static_cast<size_t>(f) * K] = sm / static_cast<float>(rec.nout); ++f; }
+        const size_t plane = static_cast<size_t>(B) * J;
+        const size_t slot = static_cast<size_t>(b) * J + jid;
+        partials[slot] = m;
+        reinterpret_cast<int *>(partials)[plane + slot] = cn;
+        partials[2 * plane + slot] = sm;
     }
 }
-

@@ -5,11 +5,12 @@
 #include "rocket_forward_impl.hpp"
 
 int rk_launch_forward_short(const rocket_kernels *h, const float *xpad, int32_t B, uint32_t mask, float nl, float ns,
-                            float *out, void *stream_ptr)
+                            float *partials, void *stream_ptr)
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_ptr);
-    hipLaunchKernelGGL(rk_forward<64>, dim3(static_cast<unsigned>(B) * h->K), dim3(64), 0, stream, xpad,
-                       static_cast<int>(h->row_len), h->lead, h->L, h->C, h->K, h->d_rec, h->d_order, h->d_channels,
-                       h->d_weights, mask, nl, ns, out);
+    const int J = static_cast<int>(h->jobs.size());
+    hipLaunchKernelGGL(rk_forward<64>, dim3(static_cast<unsigned>(B) * J), dim3(64), 0, stream, xpad,
+                       static_cast<int>(h->row_len), h->lead, h->L, h->C, J, h->d_rec, h->d_jobs, h->d_channels,
+                       h->d_weights, mask, nl, ns, partials, B);
     return hipGetLastError() == hipSuccess ? ROCKET_OK : ROCKET_EHIP;
 }

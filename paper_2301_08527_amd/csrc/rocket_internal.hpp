@@ -7,6 +7,23 @@
 
 #include "rocket.h"
 
+// Constants shared by the host planner and the kernels.
+#ifndef RK_LDS_ROWS
+#define RK_LDS_ROWS 17
+#endif
+#ifndef RK_LDS_MAXD
+#define RK_LDS_MAXD 16
+#endif
+constexpr int kThreads = 256;                 // lanes of the standard workgroup
+constexpr int kLdsRows = RK_LDS_ROWS;         // rows per band in the LDS path
+constexpr int kLdsMaxD = RK_LDS_MAXD;         // dilations below this take the LDS path
+constexpr int kFewMinD = 256;                 // few-rows path: smallest dilation ...
+constexpr int kFewRowsMax = 24;               // ... and largest number of output rows
+#ifndef RK_TILE_POSITIONS
+#define RK_TILE_POSITIONS 16384
+#endif
+constexpr int64_t kTilePositions = RK_TILE_POSITIONS;   // smallest time tile of a forward job, in output positions
+
 // One packed record per kernel as the device code reads it (32 bytes).
 struct RkKernelRec {
     int32_t len, dil, pad, nout;
@@ -14,6 +31,14 @@ struct RkKernelRec {
     int32_t nch;
     int32_t ch_off;  // into channels[]
     int32_t w_off;   // into weights[]
+};
+
+// One forward work item: rows [row0, row1) of kernel `kernel` (rows of d consecutive
+// output positions); 16 bytes.
+struct RkJob {
+    int32_t kernel;
+    int32_t row0, row1;
+    int32_t flags;   // bit 0: also owns the partial last row; bit 1: covers the whole kernel
 };
 
 struct rocket_kernels {
@@ -24,6 +49,10 @@ struct rocket_kernels {
 
     // plan: kernels in launch order (most expensive first), padded row geometry
     std::vector<int32_t> order;
+    // forward plan: every kernel's rows cut into time tiles; jobs sorted by time window so
+    // that workgroups running together read the same stretch of the series
+    std::vector<RkJob> jobs;
+    std::vector<int32_t> kjob_off, kjob_idx;   // jobs of kernel k: kjob_idx[kjob_off[k] .. kjob_off[k+1])
     int32_t pad_max = 0;     // largest padding of any kernel
     int32_t lead = 0;        // zeros in front of every padded row (multiple of 64)
     int64_t row_len = 0;     // floats per padded row (multiple of 64)
@@ -38,6 +67,9 @@ struct rocket_kernels {
     bool params_dirty = true;
     const RkKernelRec *d_rec = nullptr;
     const int32_t *d_order = nullptr;
+    const RkJob *d_jobs = nullptr;
+    const int32_t *d_kjob_off = nullptr;
+    const int32_t *d_kjob_idx = nullptr;
     const int32_t *d_channels = nullptr;
     float *d_weights = nullptr;
 
@@ -57,11 +89,16 @@ int rk_finish_handle(rocket_kernels &h);
 // Kernel launchers (rocket_forward.hip, rocket_backward.hip).  `stream` is a hipStream_t.
 // They enqueue and return ROCKET_OK, or ROCKET_EHIP if the launch itself was rejected.
 int rk_launch_pad(const rocket_kernels *h, const float *x, int32_t B, float *xpad, void *stream);
+// forward kernel: one workgroup per (series, job); writes per-job partial results
+// (max, positive count, sigmoid sum: three planes of B*J words) into `partials`
 int rk_launch_forward(const rocket_kernels *h, const float *xpad, int32_t B, uint32_t mask, float nl, float ns,
-                      float *out, void *stream);
-// same kernel with one wavefront per (series, kernel), for short series
+                      float *partials, void *stream);
+// same kernel with one wavefront per workgroup, for short series
 int rk_launch_forward_short(const rocket_kernels *h, const float *xpad, int32_t B, uint32_t mask, float nl, float ns,
-                            float *out, void *stream);
+                            float *partials, void *stream);
+// combines the per-job partials of every (series, kernel) into the feature planes
+int rk_launch_finalize(const rocket_kernels *h, const float *partials, int32_t B, uint32_t mask, float *out,
+                       void *stream);
 int rk_launch_backward(const rocket_kernels *h, const float *xpad, int32_t B, const float *grad_out, int F,
                        int plane_soft, int plane_max, float lambda, float nl, float ns, float *partial, void *stream);
 int rk_launch_reduce_batch(const rocket_kernels *h, const float *partial, int32_t B, float *grad_w, float *grad_b,

@@ -14,7 +14,8 @@ ROCKET_F_MAX, ROCKET_F_PPV, ROCKET_F_SOFTPPV = 1, 2, 4
 ROCKET_OK, ROCKET_EINVAL, ROCKET_ENOMEM, ROCKET_EHIP, ROCKET_ESHAPE, ROCKET_EWORKSPACE = 0, -1, -2, -3, -4, -5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "librocket_mi355x.so")
+# the in-tree library; the environment variable ROCKET_LIB names another build of it
+LIB_PATH = os.environ.get("ROCKET_LIB") or os.path.join(_HERE, "librocket_mi355x.so")
 
 EXPORTS = [
     "rocket_make_kernels", "rocket_kernels_import", "rocket_kernels_view_get",
