@@ -54,6 +54,9 @@ static inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * 
 int rk_finish_handle(rocket_kernels &h)
 {
     const int32_t K = h.K;
+    // byte offsets inside a padded row (up to 42 dilation steps of at most L/6 floats)
+    // are 32-bit in the kernels
+    if (h.L > 100000000) return rk_fail(ROCKET_EINVAL, "series longer than 100,000,000 samples are not supported");
     h.ch_off.assign(K + 1, 0);
     h.w_off.assign(K + 1, 0);
     h.pad_max = 0;
