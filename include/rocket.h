@@ -169,6 +169,25 @@ int rocket_work_per_series(const rocket_kernels *kernels, double *conv_fma, doub
 int rocket_profile_enable(rocket_kernels *kernels, int enable);
 int rocket_profile_read(rocket_kernels *kernels, int32_t *launches, double *total_ms);
 
+/*
+ * Ridge regressor on the pooled features (paper section 3 part (3), section 3.3):
+ * minimises ||y - X w - b||^2 + alpha ||w||^2 over (w, b), the intercept b unpenalised.
+ * features_dev: device, n x p float32 row-major (the transform's output for n series);
+ * targets_dev: device, n float32; alpha > 0.  coef_dev (device, p doubles) and
+ * intercept_dev (device, 1 double) receive w and b.  All arithmetic is fp64; the fit
+ * solves the n x n dual system, so it needs n <= 4096 (the paper has 677 training
+ * examples and p = 20,000).  workspace_dev: rocket_ridge_workspace_bytes(n, p) bytes of
+ * device memory, 256-byte aligned.  Asynchronous on hip_stream like the other calls.
+ */
+size_t rocket_ridge_workspace_bytes(int32_t n, int32_t p);
+int rocket_ridge_fit(const float *features_dev, const float *targets_dev, int32_t n, int32_t p, double alpha,
+                     double *coef_dev, double *intercept_dev, void *workspace_dev, size_t workspace_bytes,
+                     void *hip_stream);
+
+/* Predictions pred_dev[i] = b + features_dev[i] . w for m rows (device pointers; fp64 out). */
+int rocket_ridge_predict(const float *features_dev, int32_t m, int32_t p, const double *coef_dev,
+                         const double *intercept_dev, double *pred_dev, void *hip_stream);
+
 /* Frees a handle and its device mirror; NULL is allowed. */
 void rocket_free_kernels(rocket_kernels *kernels);
 

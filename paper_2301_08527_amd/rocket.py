@@ -22,6 +22,7 @@ EXPORTS = [
     "rocket_kernels_set_params", "rocket_num_features", "rocket_workspace_bytes",
     "rocket_transform", "rocket_soft_ppv_backward", "rocket_work_per_series",
     "rocket_profile_enable", "rocket_profile_read",
+    "rocket_ridge_workspace_bytes", "rocket_ridge_fit", "rocket_ridge_predict",
     "rocket_free_kernels", "rocket_last_error",
 ]
 
@@ -70,6 +71,10 @@ def load_library():
     lib.rocket_work_per_series.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.rocket_profile_enable.argtypes = [vp, C.c_int]
     lib.rocket_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]
+    lib.rocket_ridge_workspace_bytes.argtypes = [i32, i32]
+    lib.rocket_ridge_workspace_bytes.restype = C.c_size_t
+    lib.rocket_ridge_fit.argtypes = [vp, vp, i32, i32, C.c_double, vp, vp, vp, C.c_size_t, vp]
+    lib.rocket_ridge_predict.argtypes = [vp, i32, i32, vp, vp, vp, vp]
     lib.rocket_free_kernels.argtypes = [vp]
     lib.rocket_free_kernels.restype = None
     lib.rocket_last_error.restype = C.c_char_p
@@ -245,6 +250,42 @@ def rocket_soft_ppv_backward(kernels, x, feature_mask, grad_out, lam=10.0, shift
         grad_w.data_ptr(), grad_b.data_ptr(), workspace.data_ptr(),
         workspace.numel() * workspace.element_size(), _stream_ptr(torch, stream)))
     return grad_w, grad_b
+
+
+def rocket_ridge_workspace_bytes(n, p):
+    return int(load_library().rocket_ridge_workspace_bytes(n, p))
+
+
+def rocket_ridge_fit(features, targets, alpha, workspace=None, stream=None):
+    """features: float32 CUDA (n, p); targets: float32 CUDA (n).  Returns (coef [p], intercept [1]) float64 CUDA."""
+    torch = _torch()
+    if not (features.is_cuda and features.dtype == torch.float32 and features.is_contiguous() and features.dim() == 2):
+        raise RocketError(ROCKET_EINVAL, "features must be a contiguous float32 CUDA tensor (n, p)")
+    n, p = features.shape
+    if not (targets.is_cuda and targets.dtype == torch.float32 and targets.is_contiguous() and tuple(targets.shape) == (n,)):
+        raise RocketError(ROCKET_EINVAL, "targets must be a contiguous float32 CUDA tensor (n,)")
+    coef = torch.empty(p, dtype=torch.float64, device=features.device)
+    intercept = torch.empty(1, dtype=torch.float64, device=features.device)
+    if workspace is None:
+        workspace = torch.empty(rocket_ridge_workspace_bytes(n, p), dtype=torch.uint8, device=features.device)
+    _check(load_library().rocket_ridge_fit(features.data_ptr(), targets.data_ptr(), n, p, float(alpha), coef.data_ptr(),
+                                           intercept.data_ptr(), workspace.data_ptr(),
+                                           workspace.numel(), _stream_ptr(torch, stream)))
+    return coef, intercept
+
+
+def rocket_ridge_predict(features, coef, intercept, stream=None):
+    """Returns float64 CUDA predictions (m,) for float32 CUDA features (m, p)."""
+    torch = _torch()
+    if not (features.is_cuda and features.dtype == torch.float32 and features.is_contiguous() and features.dim() == 2):
+        raise RocketError(ROCKET_EINVAL, "features must be a contiguous float32 CUDA tensor (m, p)")
+    m, p = features.shape
+    if not (coef.is_cuda and coef.dtype == torch.float64 and coef.numel() == p and intercept.dtype == torch.float64):
+        raise RocketError(ROCKET_EINVAL, "coef must be float64 CUDA of length p, intercept float64")
+    pred = torch.empty(m, dtype=torch.float64, device=features.device)
+    _check(load_library().rocket_ridge_predict(features.data_ptr(), m, p, coef.data_ptr(), intercept.data_ptr(),
+                                               pred.data_ptr(), _stream_ptr(torch, stream)))
+    return pred
 
 
 def rocket_free_kernels(kernels):
