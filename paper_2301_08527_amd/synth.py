@@ -88,6 +88,22 @@ def make_input(i, B=None):
     return out
 
 
+def make_input_u8(i, B=None):
+    """uint8 array (B, C, L): workload i before normalisation, as 8-bit sensor intensities
+    (the paper's raw data are integers 0..255): each channel gets its own gain and offset,
+    is clipped to the sensor range and rounded."""
+    cfg = CONFIGS[i]
+    B = cfg["B"] if B is None else B
+    out = np.empty((B, cfg["C"], cfg["L"]), np.uint8)
+    for b in range(B):
+        a = _example(i, b)
+        rng = np.random.Generator(np.random.PCG64([seed_x(i), b, 8]))
+        gain = rng.uniform(15.0, 45.0, size=(cfg["C"], 1))
+        offset = rng.uniform(90.0, 160.0, size=(cfg["C"], 1))
+        out[b] = np.clip(np.rint(a * gain + offset), 0, 255).astype(np.uint8)
+    return out
+
+
 def make_upstream_grad(i, B, n_features):
     """N(0,1) upstream gradient (B, n_features) float32 for the backward workloads."""
     rng = np.random.Generator(np.random.PCG64(seed_g(i)))
