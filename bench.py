@@ -24,6 +24,7 @@ WORKLOADS = {
     # name: (synth config, feature mask or None = the config's, description)
     "multivariate-20x50k": 2,
     "multivariate-20x50k-grad": 3,
+    "multivariate-20x50k-u8": 2,      # the same batch as raw 8-bit samples, normalised inside the call
     "univariate-standard": 1,
     "univariate-tiny": 0,
     "long-20x200k": 4,
@@ -49,6 +50,8 @@ def cpu_baseline(cfg_id, x_host, kr, mask, lam, n_examples):
     import oracle
     xs = x_host[:n_examples]
     t0 = time.perf_counter()
+    if xs.dtype == np.uint8:
+        xs = oracle.znormalize_u8(xs)
     oracle.transform(xs, kr, lam=lam, shift=-3.0)
     dt = time.perf_counter() - t0
     return {
@@ -79,7 +82,8 @@ def main():
     mask = cfg["features"] if args.features is None else args.features
     K, C, L = cfg["K"], cfg["C"], cfg["L"]
 
-    x_host = synth.make_input(cfg_id, B=B)
+    from_u8 = args.workload.endswith("-u8")
+    x_host = synth.make_input_u8(cfg_id, B=B) if from_u8 else synth.make_input(cfg_id, B=B)
     h = rocket.rocket_make_kernels(synth.seed_k(cfg_id), K, C, L)
     fma_per_series, outputs_per_series = rocket.rocket_work_per_series(h)
     F = rocket.rocket_num_features(mask)
@@ -103,8 +107,10 @@ def main():
         rocket.rocket_soft_ppv_backward(h, x, mask, gout, args.lam, -3.0, True, grad_w=gw, grad_b=gb,
                                         workspace=ws, stream=stream)
 
+    transform = rocket.rocket_transform_u8 if from_u8 else rocket.rocket_transform
+
     def step():
-        rocket.rocket_transform(h, x, mask, args.lam, -3.0, out=out, workspace=ws, stream=stream)
+        transform(h, x, mask, args.lam, -3.0, out=out, workspace=ws, stream=stream)
         if with_grad:
             backward()
 

@@ -110,7 +110,8 @@ int32_t rocket_num_features(uint32_t feature_mask);
  * Returns 0 on invalid arguments.  The workspace holds a zero-padded copy of
  * the batch (so that dilated reads never leave a row) and partial results: for
  * the transform the pooled values of every (series, time tile of a kernel), for
- * the backward pass per-series partial gradients.  Its contents are scratch.
+ * the backward pass per-series partial gradients; and 16 bytes per (series,
+ * channel) row for the statistics of the 8-bit entry points.  Its contents are scratch.
  */
 size_t rocket_workspace_bytes(const rocket_kernels *kernels, int32_t B, uint32_t feature_mask, int backward);
 
@@ -144,13 +145,33 @@ int rocket_transform(rocket_kernels *kernels, const float *x_dev, int32_t B, uin
  * the layout of `weights`; grad_b_dev: device, K floats.  No gradient with
  * respect to x.  workspace: rocket_workspace_bytes(kernels, B, mask, 1) bytes.
  * Kernels with more than 9 channels (possible only through rocket_kernels_import)
- * are rejected with ROCKET_ESHAPE.  Sums over positions use LDS atomic adds, so two
- * runs agree up to fp32 rounding order; the sum over the batch is in a fixed order.
+ * are rejected with ROCKET_ESHAPE.  Every sum (over positions, over the batch) is taken
+ * in a fixed order without atomics, so two runs on the same inputs agree bit for bit.
  */
 int rocket_soft_ppv_backward(rocket_kernels *kernels, const float *x_dev, int32_t B, uint32_t feature_mask,
                              const float *grad_out_dev, float lambda, float shift, int include_max,
                              float *grad_w_dev, float *grad_b_dev,
                              void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The same two calls for raw 8-bit samples with the input prologue fused in.  The paper's
+ * examples are integer light intensities and every channel of every example is
+ * z-normalised before the transform (sections 4.1 and 4.3).  x_u8_dev is device memory,
+ * B x C x L uint8; each (series, channel) row is replaced by (x - mean) / std with its own
+ * mean and population standard deviation (divide by L; exact integer sums, then fp64,
+ * rounded once to fp32), a row of zero variance by zeros, and the result is transformed
+ * exactly as the float32 entry points do.  The normalised values exist only in the padded
+ * workspace copy: the batch is read as one byte per sample and no fp32 batch is stored.
+ * All other arguments, the workspace size and the error behaviour are those of
+ * rocket_transform and rocket_soft_ppv_backward.
+ */
+int rocket_transform_u8(rocket_kernels *kernels, const uint8_t *x_u8_dev, int32_t B, uint32_t feature_mask,
+                        float lambda, float shift, float *out_dev,
+                        void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+int rocket_soft_ppv_backward_u8(rocket_kernels *kernels, const uint8_t *x_u8_dev, int32_t B, uint32_t feature_mask,
+                                const float *grad_out_dev, float lambda, float shift, int include_max,
+                                float *grad_w_dev, float *grad_b_dev,
+                                void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
 /* Algorithmic work of one call, for roofline accounting: *conv_fma receives
  * sum_k n_k*n_ch_k*len_k (fused multiply-adds per series of the forward conv),

@@ -14,7 +14,8 @@ COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-KERNEL_TUS = ("rocket_forward.hip", "rocket_forward_short.hip", "rocket_backward.hip", "rocket_ridge.hip")   # translation units that hold device code
+KERNEL_TUS = ("rocket_forward.hip", "rocket_forward_short.hip", "rocket_backward.hip", "rocket_ridge.hip",
+              "rocket_prologue.hip")   # translation units that hold device code
 HOST_TUS = ("rocket_api.hip",)
 
 

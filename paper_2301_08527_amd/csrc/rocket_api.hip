@@ -336,7 +336,8 @@ extern "C" void rocket_free_kernels(rocket_kernels *h)
     delete h;
 }
 
-// workspace layout: [padded batch: B*C*row_len floats][backward: B*(total_w + 2K) floats]
+// workspace layout: [padded batch: B*C*row_len floats][partial results of the forward or the
+// backward kernel][mean and standard deviation of every row, used by the 8-bit entry points]
 static size_t padded_batch_bytes(const rocket_kernels *h, int32_t B)
 {
     // 8 KB of slack: the LDS staging of the last row may read a few hundred floats past it
@@ -348,12 +349,17 @@ static size_t backward_partial_floats(const rocket_kernels *h) { return static_c
 // forward: three words (max, positive count, sigmoid sum) per (series, job)
 static size_t forward_partial_floats(const rocket_kernels *h) { return 3 * h->jobs.size(); }
 
-extern "C" size_t rocket_workspace_bytes(const rocket_kernels *h, int32_t B, uint32_t mask, int backward)
+static size_t row_stats_offset(const rocket_kernels *h, int32_t B, int backward)
 {
-    if (!h || B < 1 || rocket_num_features(mask) == 0) return 0;
     size_t bytes = padded_batch_bytes(h, B);
     bytes += static_cast<size_t>(B) * (backward ? backward_partial_floats(h) : forward_partial_floats(h)) * 4;
     return static_cast<size_t>(round_up(static_cast<int64_t>(bytes), 256));
+}
+
+extern "C" size_t rocket_workspace_bytes(const rocket_kernels *h, int32_t B, uint32_t mask, int backward)
+{
+    if (!h || B < 1 || rocket_num_features(mask) == 0) return 0;
+    return row_stats_offset(h, B, backward) + static_cast<size_t>(round_up(static_cast<int64_t>(B) * h->C * 16, 256));
 }
 
 // ------------------------------------------------------------------ device mirror
@@ -434,18 +440,31 @@ static int check_common(const char *fn, const rocket_kernels *h, const void *x, 
     return ROCKET_OK;
 }
 
-extern "C" int rocket_transform(rocket_kernels *h, const float *x_dev, int32_t B, uint32_t mask, float lambda,
-                                float shift, float *out_dev, void *ws, size_t ws_bytes, void *hip_stream)
+// Fills the padded workspace copy from fp32 samples, or from 8-bit samples with the
+// per-row z-normalisation folded in.
+static int pad_batch(const rocket_kernels *h, const void *x_dev, bool is_u8, int32_t B, void *ws, int backward,
+                     hipStream_t stream)
 {
-    int rc = check_common("rocket_transform", h, x_dev, B, mask, lambda, shift, ws, ws_bytes, 0);
+    float *xpad = static_cast<float *>(ws);
+    const int rc = is_u8 ? rk_launch_pad_u8(h, static_cast<const uint8_t *>(x_dev), B, xpad,
+                                            static_cast<char *>(ws) + row_stats_offset(h, B, backward), stream)
+                         : rk_launch_pad(h, static_cast<const float *>(x_dev), B, xpad, stream);
+    return rc == ROCKET_OK ? ROCKET_OK : rk_fail(ROCKET_EHIP, "launch of the padding kernel failed");
+}
+
+static int transform_impl(const char *fn, rocket_kernels *h, const void *x_dev, bool is_u8, int32_t B, uint32_t mask,
+                          float lambda, float shift, float *out_dev, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    int rc = check_common(fn, h, x_dev, B, mask, lambda, shift, ws, ws_bytes, 0);
     if (rc != ROCKET_OK) return rc;
-    if (!out_dev) return rk_fail(ROCKET_EINVAL, "rocket_transform: out_dev is NULL");
-    if (h->row_len > INT32_MAX) return rk_fail(ROCKET_EINVAL, "rocket_transform: series too long");
+    if (!out_dev) return rk_fail(ROCKET_EINVAL, std::string(fn) + ": out_dev is NULL");
+    if (h->row_len > INT32_MAX) return rk_fail(ROCKET_EINVAL, std::string(fn) + ": series too long");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     rc = ensure_device(h, stream);
     if (rc != ROCKET_OK) return rc;
     float *xpad = static_cast<float *>(ws);
-    if (rk_launch_pad(h, x_dev, B, xpad, stream) != ROCKET_OK) return rk_fail(ROCKET_EHIP, "launch of the padding kernel failed");
+    rc = pad_batch(h, x_dev, is_u8, B, ws, 0, stream);
+    if (rc != ROCKET_OK) return rc;
     const float nl = -lambda * kLog2e, ns = -shift * kLog2e;
     rc = profile_mark(h, stream, true);
     if (rc != ROCKET_OK) return rc;
@@ -461,25 +480,39 @@ extern "C" int rocket_transform(rocket_kernels *h, const float *x_dev, int32_t B
     return ROCKET_OK;
 }
 
-extern "C" int rocket_soft_ppv_backward(rocket_kernels *h, const float *x_dev, int32_t B, uint32_t mask,
-                                        const float *grad_out_dev, float lambda, float shift, int include_max,
-                                        float *grad_w_dev, float *grad_b_dev, void *ws, size_t ws_bytes,
-                                        void *hip_stream)
+extern "C" int rocket_transform(rocket_kernels *h, const float *x_dev, int32_t B, uint32_t mask, float lambda,
+                                float shift, float *out_dev, void *ws, size_t ws_bytes, void *hip_stream)
 {
-    int rc = check_common("rocket_soft_ppv_backward", h, x_dev, B, mask, lambda, shift, ws, ws_bytes, 1);
+    return transform_impl("rocket_transform", h, x_dev, false, B, mask, lambda, shift, out_dev, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int rocket_transform_u8(rocket_kernels *h, const uint8_t *x_u8_dev, int32_t B, uint32_t mask, float lambda,
+                                   float shift, float *out_dev, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return transform_impl("rocket_transform_u8", h, x_u8_dev, true, B, mask, lambda, shift, out_dev, ws, ws_bytes,
+                          hip_stream);
+}
+
+static int backward_impl(const char *fn, rocket_kernels *h, const void *x_dev, bool is_u8, int32_t B, uint32_t mask,
+                         const float *grad_out_dev, float lambda, float shift, int include_max, float *grad_w_dev,
+                         float *grad_b_dev, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    const std::string who(fn);
+    int rc = check_common(fn, h, x_dev, B, mask, lambda, shift, ws, ws_bytes, 1);
     if (rc != ROCKET_OK) return rc;
-    if (!(mask & ROCKET_F_SOFTPPV)) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: mask must contain ROCKET_F_SOFTPPV");
-    if (include_max && !(mask & ROCKET_F_MAX)) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: include_max needs ROCKET_F_MAX in the mask");
-    if (!grad_out_dev || !grad_w_dev || !grad_b_dev) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: NULL gradient pointer");
-    if (h->row_len > INT32_MAX) return rk_fail(ROCKET_EINVAL, "rocket_soft_ppv_backward: series too long");
+    if (!(mask & ROCKET_F_SOFTPPV)) return rk_fail(ROCKET_EINVAL, who + ": mask must contain ROCKET_F_SOFTPPV");
+    if (include_max && !(mask & ROCKET_F_MAX)) return rk_fail(ROCKET_EINVAL, who + ": include_max needs ROCKET_F_MAX in the mask");
+    if (!grad_out_dev || !grad_w_dev || !grad_b_dev) return rk_fail(ROCKET_EINVAL, who + ": NULL gradient pointer");
+    if (h->row_len > INT32_MAX) return rk_fail(ROCKET_EINVAL, who + ": series too long");
     if (h->max_terms > kBwdMaxTerms)
-        return rk_fail(ROCKET_ESHAPE, "rocket_soft_ppv_backward: a kernel has more than 9 channels x 11 weights");
+        return rk_fail(ROCKET_ESHAPE, who + ": a kernel has more than 9 channels x 11 weights");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     rc = ensure_device(h, stream);
     if (rc != ROCKET_OK) return rc;
     float *xpad = static_cast<float *>(ws);
     float *partial = reinterpret_cast<float *>(static_cast<char *>(ws) + padded_batch_bytes(h, B));
-    if (rk_launch_pad(h, x_dev, B, xpad, stream) != ROCKET_OK) return rk_fail(ROCKET_EHIP, "launch of the padding kernel failed");
+    rc = pad_batch(h, x_dev, is_u8, B, ws, 1, stream);
+    if (rc != ROCKET_OK) return rc;
     const int F = rocket_num_features(mask);
     const int plane_soft = F - 1;                 // planes are in bit order: softPPV is last
     const int plane_max = include_max ? 0 : -1;   // and max, when present, is first
@@ -493,4 +526,22 @@ extern "C" int rocket_soft_ppv_backward(rocket_kernels *h, const float *x_dev, i
     if (rk_launch_reduce_batch(h, partial, B, grad_w_dev, grad_b_dev, stream) != ROCKET_OK)
         return rk_fail(ROCKET_EHIP, "launch of the batch reduction kernel failed");
     return ROCKET_OK;
+}
+
+extern "C" int rocket_soft_ppv_backward(rocket_kernels *h, const float *x_dev, int32_t B, uint32_t mask,
+                                        const float *grad_out_dev, float lambda, float shift, int include_max,
+                                        float *grad_w_dev, float *grad_b_dev, void *ws, size_t ws_bytes,
+                                        void *hip_stream)
+{
+    return backward_impl("rocket_soft_ppv_backward", h, x_dev, false, B, mask, grad_out_dev, lambda, shift, include_max,
+                         grad_w_dev, grad_b_dev, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int rocket_soft_ppv_backward_u8(rocket_kernels *h, const uint8_t *x_u8_dev, int32_t B, uint32_t mask,
+                                           const float *grad_out_dev, float lambda, float shift, int include_max,
+                                           float *grad_w_dev, float *grad_b_dev, void *ws, size_t ws_bytes,
+                                           void *hip_stream)
+{
+    return backward_impl("rocket_soft_ppv_backward_u8", h, x_u8_dev, true, B, mask, grad_out_dev, lambda, shift,
+                         include_max, grad_w_dev, grad_b_dev, ws, ws_bytes, hip_stream);
 }

@@ -89,6 +89,9 @@ int rk_finish_handle(rocket_kernels &h);
 // Kernel launchers (rocket_forward.hip, rocket_backward.hip).  `stream` is a hipStream_t.
 // They enqueue and return ROCKET_OK, or ROCKET_EHIP if the launch itself was rejected.
 int rk_launch_pad(const rocket_kernels *h, const float *x, int32_t B, float *xpad, void *stream);
+// rocket_prologue.hip: the same copy from 8-bit samples, z-normalising every row on the way;
+// `stats` is device scratch of 16 bytes per (series, channel) row
+int rk_launch_pad_u8(const rocket_kernels *h, const uint8_t *x, int32_t B, float *xpad, void *stats, void *stream);
 // forward kernel: one workgroup per (series, job); writes per-job partial results
 // (max, positive count, sigmoid sum: three planes of B*J words) into `partials`
 int rk_launch_forward(const rocket_kernels *h, const float *xpad, int32_t B, uint32_t mask, float nl, float ns,

@@ -20,7 +20,8 @@ LIB_PATH = os.environ.get("ROCKET_LIB") or os.path.join(_HERE, "librocket_mi355x
 EXPORTS = [
     "rocket_make_kernels", "rocket_kernels_import", "rocket_kernels_view_get",
     "rocket_kernels_set_params", "rocket_num_features", "rocket_workspace_bytes",
-    "rocket_transform", "rocket_soft_ppv_backward", "rocket_work_per_series",
+    "rocket_transform", "rocket_soft_ppv_backward", "rocket_transform_u8", "rocket_soft_ppv_backward_u8",
+    "rocket_work_per_series",
     "rocket_profile_enable", "rocket_profile_read",
     "rocket_ridge_workspace_bytes", "rocket_ridge_fit", "rocket_ridge_predict",
     "rocket_free_kernels", "rocket_last_error",
@@ -68,6 +69,8 @@ def load_library():
     lib.rocket_workspace_bytes.restype = C.c_size_t
     lib.rocket_transform.argtypes = [vp, vp, i32, u32, f32, f32, vp, vp, C.c_size_t, vp]
     lib.rocket_soft_ppv_backward.argtypes = [vp, vp, i32, u32, vp, f32, f32, C.c_int, vp, vp, vp, C.c_size_t, vp]
+    lib.rocket_transform_u8.argtypes = lib.rocket_transform.argtypes
+    lib.rocket_soft_ppv_backward_u8.argtypes = lib.rocket_soft_ppv_backward.argtypes
     lib.rocket_work_per_series.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.rocket_profile_enable.argtypes = [vp, C.c_int]
     lib.rocket_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]
@@ -204,11 +207,12 @@ def _workspace(torch, kernels, B, mask, backward, workspace, device):
     return workspace, need
 
 
-def rocket_transform(kernels, x, feature_mask, lam=10.0, shift=-3.0, out=None, workspace=None, stream=None):
+def rocket_transform(kernels, x, feature_mask, lam=10.0, shift=-3.0, out=None, workspace=None, stream=None,
+                     _dtype="float32", _entry="rocket_transform"):
     """x: float32 CUDA tensor (B, C, L), contiguous.  Returns out (B, F*K)."""
     torch = _torch()
-    if not (x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() == 3):
-        raise RocketError(ROCKET_EINVAL, "x must be a contiguous float32 CUDA tensor of shape (B, C, L)")
+    if not (x.is_cuda and x.dtype == getattr(torch, _dtype) and x.is_contiguous() and x.dim() == 3):
+        raise RocketError(ROCKET_EINVAL, "x must be a contiguous %s CUDA tensor of shape (B, C, L)" % _dtype)
     v = _View()
     _check(load_library().rocket_kernels_view_get(kernels.handle, C.byref(v)))
     B = x.shape[0]
@@ -219,19 +223,26 @@ def rocket_transform(kernels, x, feature_mask, lam=10.0, shift=-3.0, out=None, w
     if out is None:
         out = torch.empty((B, max(F, 1) * v.K), dtype=torch.float32, device=x.device)
     workspace, _ = _workspace(torch, kernels, B, feature_mask, False, workspace, x.device)
-    _check(load_library().rocket_transform(
+    _check(getattr(load_library(), _entry)(
         kernels.handle, x.data_ptr(), B, feature_mask, lam, shift, out.data_ptr(),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(torch, stream)))
     return out
 
 
+def rocket_transform_u8(kernels, x_u8, feature_mask, lam=10.0, shift=-3.0, out=None, workspace=None, stream=None):
+    """x_u8: uint8 CUDA tensor (B, C, L), contiguous; rows are z-normalised inside the call."""
+    return rocket_transform(kernels, x_u8, feature_mask, lam, shift, out, workspace, stream,
+                            _dtype="uint8", _entry="rocket_transform_u8")
+
+
 def rocket_soft_ppv_backward(kernels, x, feature_mask, grad_out, lam=10.0, shift=-3.0, include_max=False,
-                             grad_w=None, grad_b=None, workspace=None, stream=None):
+                             grad_w=None, grad_b=None, workspace=None, stream=None,
+                             _dtype="float32", _entry="rocket_soft_ppv_backward"):
     """Returns (grad_w [total_weights], grad_b [K]) as float32 CUDA tensors."""
     torch = _torch()
-    for t, name in ((x, "x"), (grad_out, "grad_out")):
-        if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
-            raise RocketError(ROCKET_EINVAL, name + " must be a contiguous float32 CUDA tensor")
+    for t, name, dt in ((x, "x", _dtype), (grad_out, "grad_out", "float32")):
+        if not (t.is_cuda and t.dtype == getattr(torch, dt) and t.is_contiguous()):
+            raise RocketError(ROCKET_EINVAL, "%s must be a contiguous %s CUDA tensor" % (name, dt))
     v = _View()
     _check(load_library().rocket_kernels_view_get(kernels.handle, C.byref(v)))
     B = x.shape[0]
@@ -245,11 +256,19 @@ def rocket_soft_ppv_backward(kernels, x, feature_mask, grad_out, lam=10.0, shift
     if grad_b is None:
         grad_b = torch.empty(v.K, dtype=torch.float32, device=x.device)
     workspace, _ = _workspace(torch, kernels, B, feature_mask, True, workspace, x.device)
-    _check(load_library().rocket_soft_ppv_backward(
+    _check(getattr(load_library(), _entry)(
         kernels.handle, x.data_ptr(), B, feature_mask, grad_out.data_ptr(), lam, shift, int(bool(include_max)),
         grad_w.data_ptr(), grad_b.data_ptr(), workspace.data_ptr(),
         workspace.numel() * workspace.element_size(), _stream_ptr(torch, stream)))
     return grad_w, grad_b
+
+
+def rocket_soft_ppv_backward_u8(kernels, x_u8, feature_mask, grad_out, lam=10.0, shift=-3.0, include_max=False,
+                                grad_w=None, grad_b=None, workspace=None, stream=None):
+    """The backward pass on uint8 samples, z-normalised inside the call."""
+    return rocket_soft_ppv_backward(kernels, x_u8, feature_mask, grad_out, lam, shift, include_max,
+                                    grad_w, grad_b, workspace, stream,
+                                    _dtype="uint8", _entry="rocket_soft_ppv_backward_u8")
 
 
 def rocket_ridge_workspace_bytes(n, p):

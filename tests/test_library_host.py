@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "rocket.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(rocket_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(rocket_[a-z0-9_]+)\s*\(", header))
     assert declared == set(rocket.EXPORTS)
     lib = rocket.load_library()
     for name in declared:
