@@ -209,6 +209,22 @@ int rocket_ridge_fit(const float *features_dev, const float *targets_dev, int32_
 int rocket_ridge_predict(const float *features_dev, int32_t m, int32_t p, const double *coef_dev,
                          const double *intercept_dev, double *pred_dev, void *hip_stream);
 
+/*
+ * Inference in one call, the use the paper builds the model for (section 4.1: one surface-
+ * roughness value per example at line speed; section 3 parts (1)-(3)): transforms a batch and
+ * applies a fitted ridge regressor, pred[b] = intercept + sum_i features[b][i] * coef[i].
+ * x_dev: device, B x C x L float32 (x_is_u8 = 0) or raw uint8 normalised as in
+ * rocket_transform_u8 (x_is_u8 = 1).  coef_dev (F*K doubles) and intercept_dev (1 double) are
+ * those of rocket_ridge_fit for the same kernels and feature mask.  features_dev (device,
+ * B x F*K float32) receives the features exactly as rocket_transform writes them; pred_dev
+ * (device, B doubles) the predictions, exactly as rocket_ridge_predict computes them from
+ * those features.  Workspace and errors as for rocket_transform.
+ */
+int rocket_infer(rocket_kernels *kernels, const void *x_dev, int x_is_u8, int32_t B, uint32_t feature_mask,
+                 float lambda, float shift, const double *coef_dev, const double *intercept_dev,
+                 float *features_dev, double *pred_dev,
+                 void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
 /* Frees a handle and its device mirror; NULL is allowed. */
 void rocket_free_kernels(rocket_kernels *kernels);
 

@@ -493,6 +493,18 @@ extern "C" int rocket_transform_u8(rocket_kernels *h, const uint8_t *x_u8_dev, i
                           hip_stream);
 }
 
+extern "C" int rocket_infer(rocket_kernels *h, const void *x_dev, int x_is_u8, int32_t B, uint32_t mask, float lambda,
+                            float shift, const double *coef_dev, const double *intercept_dev, float *features_dev,
+                            double *pred_dev, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    if (!coef_dev || !intercept_dev || !pred_dev) return rk_fail(ROCKET_EINVAL, "rocket_infer: NULL pointer");
+    int rc = transform_impl("rocket_infer", h, x_dev, x_is_u8 != 0, B, mask, lambda, shift, features_dev, ws, ws_bytes,
+                            hip_stream);
+    if (rc != ROCKET_OK) return rc;
+    return rocket_ridge_predict(features_dev, B, rocket_num_features(mask) * h->K, coef_dev, intercept_dev, pred_dev,
+                                hip_stream);
+}
+
 static int backward_impl(const char *fn, rocket_kernels *h, const void *x_dev, bool is_u8, int32_t B, uint32_t mask,
                          const float *grad_out_dev, float lambda, float shift, int include_max, float *grad_w_dev,
                          float *grad_b_dev, void *ws, size_t ws_bytes, void *hip_stream)

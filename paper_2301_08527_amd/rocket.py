@@ -23,7 +23,7 @@ EXPORTS = [
     "rocket_transform", "rocket_soft_ppv_backward", "rocket_transform_u8", "rocket_soft_ppv_backward_u8",
     "rocket_work_per_series",
     "rocket_profile_enable", "rocket_profile_read",
-    "rocket_ridge_workspace_bytes", "rocket_ridge_fit", "rocket_ridge_predict",
+    "rocket_ridge_workspace_bytes", "rocket_ridge_fit", "rocket_ridge_predict", "rocket_infer",
     "rocket_free_kernels", "rocket_last_error",
 ]
 
@@ -78,6 +78,7 @@ def load_library():
     lib.rocket_ridge_workspace_bytes.restype = C.c_size_t
     lib.rocket_ridge_fit.argtypes = [vp, vp, i32, i32, C.c_double, vp, vp, vp, C.c_size_t, vp]
     lib.rocket_ridge_predict.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+    lib.rocket_infer.argtypes = [vp, vp, C.c_int, i32, u32, f32, f32, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.rocket_free_kernels.argtypes = [vp]
     lib.rocket_free_kernels.restype = None
     lib.rocket_last_error.restype = C.c_char_p
@@ -305,6 +306,32 @@ def rocket_ridge_predict(features, coef, intercept, stream=None):
     _check(load_library().rocket_ridge_predict(features.data_ptr(), m, p, coef.data_ptr(), intercept.data_ptr(),
                                                pred.data_ptr(), _stream_ptr(torch, stream)))
     return pred
+
+
+def rocket_infer(kernels, x, feature_mask, coef, intercept, lam=10.0, shift=-3.0, features=None, workspace=None,
+                 stream=None):
+    """x: float32 or uint8 CUDA tensor (B, C, L).  Returns (pred float64 (B,), features float32 (B, F*K))."""
+    torch = _torch()
+    if not (x.is_cuda and x.dtype in (torch.float32, torch.uint8) and x.is_contiguous() and x.dim() == 3):
+        raise RocketError(ROCKET_EINVAL, "x must be a contiguous float32 or uint8 CUDA tensor of shape (B, C, L)")
+    v = _View()
+    _check(load_library().rocket_kernels_view_get(kernels.handle, C.byref(v)))
+    B = x.shape[0]
+    if x.shape[1] != v.C or x.shape[2] != v.L:
+        raise RocketError(ROCKET_ESHAPE, "x does not match the kernels' (C, L)")
+    p = rocket_num_features(feature_mask) * v.K
+    if not (coef.is_cuda and coef.dtype == torch.float64 and coef.numel() == p and coef.is_contiguous()
+            and intercept.is_cuda and intercept.dtype == torch.float64 and intercept.numel() == 1):
+        raise RocketError(ROCKET_EINVAL, "coef must be float64 CUDA of length F*K, intercept float64 CUDA of length 1")
+    if features is None:
+        features = torch.empty((B, max(p, 1)), dtype=torch.float32, device=x.device)
+    pred = torch.empty(B, dtype=torch.float64, device=x.device)
+    workspace, _ = _workspace(torch, kernels, B, feature_mask, False, workspace, x.device)
+    _check(load_library().rocket_infer(
+        kernels.handle, x.data_ptr(), int(x.dtype == torch.uint8), B, feature_mask, lam, shift,
+        coef.data_ptr(), intercept.data_ptr(), features.data_ptr(), pred.data_ptr(),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(torch, stream)))
+    return pred, features
 
 
 def rocket_free_kernels(kernels):

@@ -66,3 +66,61 @@ def test_argument_errors():
         rocket.rocket_ridge_fit(torch.zeros(5000, 2, device="cuda"), torch.zeros(5000, device="cuda"), 1.0)
     with pytest.raises(rocket.RocketError):
         rocket.rocket_ridge_fit(X, y, 1.0, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+
+
+def _oracle_features(z, kr, mask):
+    """(B, F*K) fp64 feature matrix in the library's plane order, and its per-entry parity tolerance"""
+    o = oracle.transform(z, kr)
+    n = o["n_out"][None, :].astype(np.float64)
+    cols, tols = [], []
+    if mask & 1:
+        cols.append(o["max"]); tols.append(1e-4 * np.abs(o["max"]) + 1e-5)
+    if mask & 2:
+        cols.append(o["count"] / n); tols.append(o["ambiguous"] / n)
+    if mask & 4:
+        cols.append(o["softppv"]); tols.append(1e-4 * np.abs(o["softppv"]) + 1e-5)
+    return np.concatenate(cols, axis=1), np.concatenate(tols, axis=1)
+
+
+@pytest.mark.parametrize("mask", [3, 7])
+def test_infer_from_bytes_to_prediction(mask):
+    """The whole model in one call: raw 8-bit examples -> features -> ridge prediction, against
+    the oracle pipeline (z-normalise, transform, fit, predict) with the oracle's coefficients."""
+    import torch
+    rng = np.random.default_rng(123)
+    n_train, n_test, C, L, K = 48, 9, 4, 801, 300
+    raw = rng.integers(0, 256, size=(n_train + n_test, C, L)).astype(np.uint8)
+    smooth = rng.random(n_train + n_test)                      # per-example roughness-like factor
+    for i, s in enumerate(smooth):                              # smoother examples have a lower target
+        w = 1 + int(12 * (1 - s))
+        raw[i] = np.clip(np.apply_along_axis(lambda r: np.convolve(r, np.ones(w) / w, "same"), -1,
+                                             raw[i].astype(np.float64)), 0, 255).astype(np.uint8)
+    y = (0.6 + 1.2 * smooth).astype(np.float32)
+    h = rocket.rocket_make_kernels(55, K, C, L)
+    kr = rocket.rocket_kernels_view_get(h)
+    z = oracle.znormalize_u8(raw)
+    F_ref, F_tol = _oracle_features(z, kr, mask)
+    w_ref, b_ref = oracle.ridge_fit(F_ref[:n_train].astype(np.float32), y[:n_train], 1.0)
+    pred_ref = oracle.ridge_predict(F_ref[n_train:].astype(np.float32), w_ref, b_ref)
+
+    coef = torch.from_numpy(w_ref).cuda()
+    icpt = torch.tensor([b_ref], dtype=torch.float64, device="cuda")
+    x_test = torch.from_numpy(raw[n_train:]).cuda()
+    print("infer u8", mask, flush=True)
+    pred, feats = rocket.rocket_infer(h, x_test, mask, coef, icpt)
+    torch.cuda.synchronize()
+    # composition: the same bits as the two separate calls
+    feats2 = rocket.rocket_transform_u8(h, x_test, mask)
+    pred2 = rocket.rocket_ridge_predict(feats2, coef, icpt)
+    torch.cuda.synchronize()
+    assert torch.equal(feats, feats2) and torch.equal(pred, pred2)
+    # parity with the oracle pipeline: the feature tolerances propagated through the linear model
+    bound = (np.abs(w_ref)[None, :] * (F_tol[n_train:] + 1e-7 * np.abs(F_ref[n_train:]))).sum(axis=1) + 1e-8
+    err = np.abs(pred.cpu().numpy() - pred_ref)
+    assert np.all(err <= bound), (err, bound)
+    # the model is a model: it ranks the held-out examples by the planted roughness factor
+    assert np.corrcoef(pred_ref, y[n_train:])[0, 1] > 0.8
+    # float32 input through the same entry point
+    pred_f, _ = rocket.rocket_infer(h, torch.from_numpy(z[n_train:]).cuda(), mask, coef, icpt)
+    torch.cuda.synchronize()
+    assert np.all(np.abs(pred_f.cpu().numpy() - pred_ref) <= bound)
