@@ -6,6 +6,7 @@ only tests, the smoke check and the benchmark's cpu_baseline leg import it.
 from .sampler import sample_kernel, sample_kernels  # noqa: F401
 from .ridge import ridge_fit, ridge_predict  # noqa: F401
 from .prologue import znormalize_u8  # noqa: F401
+from .train import feature_matrix, mse_loss_grad, sgd_update, loss_of, train_step  # noqa: F401
 from .rocket_oracle import (  # noqa: F401
     conv_output, transform, backward, num_threads, set_threads, AMBIGUOUS_EPS,
 )
