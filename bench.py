@@ -24,6 +24,7 @@ WORKLOADS = {
     # name: (synth config, feature mask or None = the config's, description)
     "multivariate-20x50k": 2,
     "multivariate-20x50k-grad": 3,
+    "multivariate-20x50k-train": 3,   # whole training step: transform, linear head, loss gradient, backward, update
     "multivariate-20x50k-u8": 2,      # the same batch as raw 8-bit samples, normalised inside the call
     "univariate-standard": 1,
     "univariate-tiny": 0,
@@ -109,7 +110,20 @@ def main():
 
     transform = rocket.rocket_transform_u8 if from_u8 else rocket.rocket_transform
 
+    train = args.workload.endswith("-train")
+    if train:
+        # a fixed random linear head and roughness-like targets; a small learning rate, re-centred rows
+        rng = np.random.Generator(np.random.PCG64(synth.seed_g(cfg_id)))
+        coef = torch.from_numpy(rng.standard_normal(F * K) * 0.01).to(dev)
+        icpt = torch.tensor([1.2], dtype=torch.float64, device=dev)
+        targets = torch.from_numpy((0.6 + 1.2 * rng.random(B)).astype(np.float32)).to(dev)
+        train_ws = torch.empty(rocket.rocket_train_workspace_bytes(h, B, mask), dtype=torch.uint8, device=dev)
+
     def step():
+        if train:
+            rocket.rocket_train_step(h, x, mask, coef, icpt, targets, 1e-3, args.lam, -3.0, True,
+                                     workspace=train_ws, stream=stream)
+            return
         transform(h, x, mask, args.lam, -3.0, out=out, workspace=ws, stream=stream)
         if with_grad:
             backward()
@@ -152,6 +166,7 @@ def main():
 
     line = {
         "metric": ("examples/sec (20ch x 50k, K=10k) and % of FP32 vector peak" if cfg_id == 2 else
+                   "examples/sec, whole training step through softPPV (20ch x 50k, K=10k)" if train else
                    "examples/sec, forward + softPPV backward (20ch x 50k, K=10k)" if cfg_id == 3 else
                    "series/sec" if cfg_id in (0, 1) else "examples/sec"),
         "value": value, "unit": "examples/s" if cfg_id != 1 and cfg_id != 0 else "series/s",

@@ -225,6 +225,51 @@ int rocket_infer(rocket_kernels *kernels, const void *x_dev, int x_is_u8, int32_
                  float *features_dev, double *pred_dev,
                  void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Training the kernel weights through softPPV.  Section 3.2 replaces the step function by a
+ * sigmoid so that gradients can flow, and section 6 names training the weights as the thing
+ * to try next; these calls are one plain instance of it: the features feed a fixed linear
+ * head (coef, intercept, e.g. from rocket_ridge_fit), the loss is the mean squared error of
+ * its predictions, and weights and biases move one gradient-descent step.
+ *
+ * rocket_mse_grad: pred_dev (device, B doubles), targets_dev (device, B float32), coef_dev
+ * (device, p doubles) -> grad_out_dev[b*p + i] = (2/B) (pred[b] - y[b]) coef[i] (device,
+ * B x p float32, the layout rocket_soft_ppv_backward takes) and, if loss_dev is not NULL,
+ * *loss_dev = (1/B) sum_b (pred[b] - y[b])^2 (device, 1 double).  B <= 65535.
+ *
+ * rocket_sgd_update: w <- w - lr*grad_w, b <- b - lr*grad_b on the handle's device copy of
+ * the parameters (grad_w_dev: total_weights float32, grad_b_dev: K float32, as written by
+ * rocket_soft_ppv_backward); with recentre != 0 every (kernel, channel) row of weights then has
+ * its mean subtracted, which keeps the sampler's invariant of section 3.1.  Nothing is copied
+ * to the host: later transforms on the handle use the new parameters, and the next
+ * rocket_kernels_view_get (or rocket_kernels_set_params, rocket_kernels_subset) first waits for
+ * the stream of the last update and downloads them.
+ *
+ * rocket_train_step: transform (feature_mask must contain ROCKET_F_SOFTPPV; the max plane, when
+ * present, sends its sub-gradient to its first arg-max, the PPV plane none), prediction, loss
+ * gradient, backward pass and update, enqueued on one stream.  x_dev is float32 (x_is_u8 = 0) or
+ * raw uint8 (x_is_u8 = 1, normalised as in rocket_transform_u8).  *loss_dev (may be NULL)
+ * receives the loss before the update.  workspace_dev: rocket_train_workspace_bytes(kernels, B,
+ * mask) bytes, 256-byte aligned.
+ */
+int rocket_mse_grad(const double *pred_dev, const float *targets_dev, const double *coef_dev, int32_t B, int32_t p,
+                    float *grad_out_dev, double *loss_dev, void *hip_stream);
+int rocket_sgd_update(rocket_kernels *kernels, const float *grad_w_dev, const float *grad_b_dev, float lr,
+                      int recentre, void *hip_stream);
+size_t rocket_train_workspace_bytes(const rocket_kernels *kernels, int32_t B, uint32_t feature_mask);
+int rocket_train_step(rocket_kernels *kernels, const void *x_dev, int x_is_u8, int32_t B, uint32_t feature_mask,
+                      float lambda, float shift, const double *coef_dev, const double *intercept_dev,
+                      const float *targets_dev, float lr, int recentre, double *loss_dev,
+                      void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Pruning (section 6: many of the random kernels are of little use to a given problem and can
+ * be dropped by the regressor's feature importance).  Creates a new handle that holds kernels
+ * index[0..count) of `kernels` (host array; any order, repeats allowed) with their current
+ * parameters.  The choice of which kernels to keep is the caller's.
+ */
+int rocket_kernels_subset(const rocket_kernels *kernels, const int32_t *index, int32_t count, rocket_kernels **out);
+
 /* Frees a handle and its device mirror; NULL is allowed. */
 void rocket_free_kernels(rocket_kernels *kernels);
 

@@ -237,9 +237,29 @@ extern "C" int rocket_kernels_import(int32_t K, int32_t C, int32_t L,
     return ROCKET_OK;
 }
 
+// After rocket_sgd_update the device mirror holds the newest parameters: fetch them.
+static int download_params(rocket_kernels *h)
+{
+    if (!h->host_stale) return ROCKET_OK;
+    int cur = 0;
+    RK_HIP(hipGetDevice(&cur));
+    if (cur != h->device) RK_HIP(hipSetDevice(h->device));
+    std::vector<RkKernelRec> rec(h->K);
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(h->update_stream));
+    if (e == hipSuccess) e = hipMemcpy(h->weights.data(), h->d_weights, h->weights.size() * 4, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(rec.data(), h->d_rec, rec.size() * sizeof(RkKernelRec), hipMemcpyDeviceToHost);
+    if (cur != h->device) (void)hipSetDevice(cur);
+    if (e != hipSuccess) return rk_fail(ROCKET_EHIP, std::string("download of the trained parameters failed: ") + hipGetErrorString(e));
+    for (int32_t k = 0; k < h->K; ++k) h->bias[k] = rec[k].bias;
+    h->host_stale = false;
+    return ROCKET_OK;
+}
+
 extern "C" int rocket_kernels_view_get(const rocket_kernels *h, rocket_kernels_view *v)
 {
     if (!h || !v) return rk_fail(ROCKET_EINVAL, "rocket_kernels_view_get: NULL argument");
+    const int rc = download_params(const_cast<rocket_kernels *>(h));
+    if (rc != ROCKET_OK) return rc;
     v->K = h->K; v->C = h->C; v->L = h->L;
     v->total_channels = h->ch_off[h->K];
     v->total_weights = h->w_off[h->K];
@@ -253,6 +273,9 @@ extern "C" int rocket_kernels_view_get(const rocket_kernels *h, rocket_kernels_v
 extern "C" int rocket_kernels_set_params(rocket_kernels *h, const float *weights, const float *bias)
 {
     if (!h) return rk_fail(ROCKET_EINVAL, "rocket_kernels_set_params: NULL handle");
+    if (weights && bias) h->host_stale = false;     // everything is overwritten
+    const int rc = download_params(h);
+    if (rc != ROCKET_OK) return rc;
     if (weights) {
         for (size_t i = 0; i < h->weights.size(); ++i)
             if (!std::isfinite(weights[i])) return rk_fail(ROCKET_EINVAL, "rocket_kernels_set_params: weight not finite");
@@ -556,4 +579,119 @@ extern "C" int rocket_soft_ppv_backward_u8(rocket_kernels *h, const uint8_t *x_u
 {
     return backward_impl("rocket_soft_ppv_backward_u8", h, x_u8_dev, true, B, mask, grad_out_dev, lambda, shift,
                          include_max, grad_w_dev, grad_b_dev, ws, ws_bytes, hip_stream);
+}
+
+// ------------------------------------------------------------------ training step
+
+extern "C" int rocket_mse_grad(const double *pred_dev, const float *targets_dev, const double *coef_dev, int32_t B,
+                               int32_t p, float *grad_out_dev, double *loss_dev, void *hip_stream)
+{
+    if (!pred_dev || !targets_dev || !coef_dev || !grad_out_dev) return rk_fail(ROCKET_EINVAL, "rocket_mse_grad: NULL pointer");
+    if (B < 1 || B > 65535 || p < 1) return rk_fail(ROCKET_EINVAL, "rocket_mse_grad: B must be in [1, 65535] and p >= 1");
+    if (rk_launch_mse_grad(pred_dev, targets_dev, coef_dev, B, p, grad_out_dev, loss_dev, hip_stream) != ROCKET_OK)
+        return rk_fail(ROCKET_EHIP, "launch of the loss gradient kernel failed");
+    return ROCKET_OK;
+}
+
+extern "C" int rocket_sgd_update(rocket_kernels *h, const float *grad_w_dev, const float *grad_b_dev, float lr,
+                                 int recentre, void *hip_stream)
+{
+    if (!h || !grad_w_dev || !grad_b_dev) return rk_fail(ROCKET_EINVAL, "rocket_sgd_update: NULL argument");
+    if (!std::isfinite(lr)) return rk_fail(ROCKET_EINVAL, "rocket_sgd_update: lr must be finite");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int rc = ensure_device(h, stream);      // uploads host-side parameters first if they are the newer ones
+    if (rc != ROCKET_OK) return rc;
+    if (h->host_stale && h->update_stream != hip_stream) {
+        // an earlier update ran on another stream: order this one after it
+        RK_HIP(hipStreamSynchronize(static_cast<hipStream_t>(h->update_stream)));
+    }
+    if (rk_launch_sgd_update(h, grad_w_dev, grad_b_dev, lr, recentre, stream) != ROCKET_OK)
+        return rk_fail(ROCKET_EHIP, "launch of the update kernel failed");
+    h->host_stale = true;
+    h->update_stream = hip_stream;
+    return ROCKET_OK;
+}
+
+// layout of the training workspace: [transform / backward workspace][features][upstream gradient]
+// [predictions][weight gradient][bias gradient], every part rounded up to 256 bytes
+struct TrainLayout {
+    size_t inner, feats, gout, pred, gw, gb, total;
+};
+
+static TrainLayout train_layout(const rocket_kernels *h, int32_t B, uint32_t mask)
+{
+    TrainLayout t;
+    const size_t p = static_cast<size_t>(rocket_num_features(mask)) * h->K;
+    t.inner = std::max(rocket_workspace_bytes(h, B, mask, 0), rocket_workspace_bytes(h, B, mask, 1));
+    t.feats = t.inner;
+    t.gout = t.feats + round_up(static_cast<int64_t>(B) * p * 4, 256);
+    t.pred = t.gout + round_up(static_cast<int64_t>(B) * p * 4, 256);
+    t.gw = t.pred + round_up(static_cast<int64_t>(B) * 8, 256);
+    t.gb = t.gw + round_up(static_cast<int64_t>(h->w_off[h->K]) * 4, 256);
+    t.total = t.gb + round_up(static_cast<int64_t>(h->K) * 4, 256);
+    return t;
+}
+
+extern "C" size_t rocket_train_workspace_bytes(const rocket_kernels *h, int32_t B, uint32_t mask)
+{
+    if (!h || B < 1 || rocket_num_features(mask) == 0) return 0;
+    return train_layout(h, B, mask).total;
+}
+
+extern "C" int rocket_train_step(rocket_kernels *h, const void *x_dev, int x_is_u8, int32_t B, uint32_t mask,
+                                 float lambda, float shift, const double *coef_dev, const double *intercept_dev,
+                                 const float *targets_dev, float lr, int recentre, double *loss_dev, void *ws,
+                                 size_t ws_bytes, void *hip_stream)
+{
+    if (!h) return rk_fail(ROCKET_EINVAL, "rocket_train_step: NULL handle");
+    if (!coef_dev || !intercept_dev || !targets_dev) return rk_fail(ROCKET_EINVAL, "rocket_train_step: NULL pointer");
+    if (B < 1 || rocket_num_features(mask) == 0 || !(mask & ROCKET_F_SOFTPPV))
+        return rk_fail(ROCKET_EINVAL, "rocket_train_step: B >= 1 and a feature mask that contains ROCKET_F_SOFTPPV required");
+    const TrainLayout t = train_layout(h, B, mask);
+    if (!ws || ws_bytes < t.total)
+        return rk_fail(ROCKET_EWORKSPACE, "rocket_train_step: workspace of " + std::to_string(t.total) + " bytes required");
+    char *base = static_cast<char *>(ws);
+    float *feats = reinterpret_cast<float *>(base + t.feats);
+    float *gout = reinterpret_cast<float *>(base + t.gout);
+    double *pred = reinterpret_cast<double *>(base + t.pred);
+    float *gw = reinterpret_cast<float *>(base + t.gw);
+    float *gb = reinterpret_cast<float *>(base + t.gb);
+    const int32_t p = rocket_num_features(mask) * h->K;
+    int rc = transform_impl("rocket_train_step", h, x_dev, x_is_u8 != 0, B, mask, lambda, shift, feats, ws, t.inner, hip_stream);
+    if (rc != ROCKET_OK) return rc;
+    rc = rocket_ridge_predict(feats, B, p, coef_dev, intercept_dev, pred, hip_stream);
+    if (rc != ROCKET_OK) return rc;
+    rc = rocket_mse_grad(pred, targets_dev, coef_dev, B, p, gout, loss_dev, hip_stream);
+    if (rc != ROCKET_OK) return rc;
+    rc = backward_impl("rocket_train_step", h, x_dev, x_is_u8 != 0, B, mask, gout, lambda, shift,
+                       (mask & ROCKET_F_MAX) ? 1 : 0, gw, gb, ws, t.inner, hip_stream);
+    if (rc != ROCKET_OK) return rc;
+    return rocket_sgd_update(h, gw, gb, lr, recentre, hip_stream);
+}
+
+// ------------------------------------------------------------------ pruning
+
+extern "C" int rocket_kernels_subset(const rocket_kernels *h, const int32_t *index, int32_t count, rocket_kernels **out)
+{
+    if (!out) return rk_fail(ROCKET_EINVAL, "rocket_kernels_subset: out is NULL");
+    *out = nullptr;
+    if (!h || !index || count < 1) return rk_fail(ROCKET_EINVAL, "rocket_kernels_subset: NULL argument or count < 1");
+    int rc = download_params(const_cast<rocket_kernels *>(h));
+    if (rc != ROCKET_OK) return rc;
+    try {
+        std::vector<int32_t> length(count), dilation(count), padding(count), n_ch(count), channels;
+        std::vector<float> bias(count), weights;
+        for (int32_t i = 0; i < count; ++i) {
+            const int32_t k = index[i];
+            if (k < 0 || k >= h->K) return rk_fail(ROCKET_EINVAL, "rocket_kernels_subset: index out of range");
+            length[i] = h->length[k]; dilation[i] = h->dilation[k]; padding[i] = h->padding[k];
+            n_ch[i] = h->n_ch[k]; bias[i] = h->bias[k];
+            channels.insert(channels.end(), h->channels.begin() + h->ch_off[k], h->channels.begin() + h->ch_off[k + 1]);
+            weights.insert(weights.end(), h->weights.begin() + h->w_off[k], h->weights.begin() + h->w_off[k + 1]);
+        }
+        return rocket_kernels_import(count, h->C, h->L, length.data(), dilation.data(), padding.data(), bias.data(),
+                                     n_ch.data(), channels.data(), weights.data(), out);
+    } catch (const std::bad_alloc &) {
+        return rk_fail(ROCKET_ENOMEM, "rocket_kernels_subset: out of host memory");
+    }
 }

@@ -64,7 +64,9 @@ struct rocket_kernels {
     int device = -1;
     void *d_blob = nullptr;
     size_t blob_bytes = 0;
-    bool params_dirty = true;
+    bool params_dirty = true;    // host parameters are newer than the device mirror
+    bool host_stale = false;     // the device mirror was updated in place (training) after the last download
+    void *update_stream = nullptr;   // stream of that update
     const RkKernelRec *d_rec = nullptr;
     const int32_t *d_order = nullptr;
     const RkJob *d_jobs = nullptr;
@@ -89,6 +91,12 @@ int rk_finish_handle(rocket_kernels &h);
 // Kernel launchers (rocket_forward.hip, rocket_backward.hip).  `stream` is a hipStream_t.
 // They enqueue and return ROCKET_OK, or ROCKET_EHIP if the launch itself was rejected.
 int rk_launch_pad(const rocket_kernels *h, const float *x, int32_t B, float *xpad, void *stream);
+// rocket_train.hip: loss gradient of a linear head, and the in-place parameter update of
+// the handle's device mirror
+int rk_launch_mse_grad(const double *pred, const float *targets, const double *coef, int32_t B, int32_t p,
+                       float *grad_out, double *loss, void *stream);
+int rk_launch_sgd_update(const rocket_kernels *h, const float *gw, const float *gb, float lr, int recentre,
+                         void *stream);
 // rocket_prologue.hip: the same copy from 8-bit samples, z-normalising every row on the way;
 // `stats` is device scratch of 16 bytes per (series, channel) row
 int rk_launch_pad_u8(const rocket_kernels *h, const uint8_t *x, int32_t B, float *xpad, void *stats, void *stream);

@@ -24,6 +24,8 @@ EXPORTS = [
     "rocket_work_per_series",
     "rocket_profile_enable", "rocket_profile_read",
     "rocket_ridge_workspace_bytes", "rocket_ridge_fit", "rocket_ridge_predict", "rocket_infer",
+    "rocket_mse_grad", "rocket_sgd_update", "rocket_train_workspace_bytes", "rocket_train_step",
+    "rocket_kernels_subset",
     "rocket_free_kernels", "rocket_last_error",
 ]
 
@@ -79,6 +81,13 @@ def load_library():
     lib.rocket_ridge_fit.argtypes = [vp, vp, i32, i32, C.c_double, vp, vp, vp, C.c_size_t, vp]
     lib.rocket_ridge_predict.argtypes = [vp, i32, i32, vp, vp, vp, vp]
     lib.rocket_infer.argtypes = [vp, vp, C.c_int, i32, u32, f32, f32, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.rocket_mse_grad.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
+    lib.rocket_sgd_update.argtypes = [vp, vp, vp, f32, C.c_int, vp]
+    lib.rocket_train_workspace_bytes.argtypes = [vp, i32, u32]
+    lib.rocket_train_workspace_bytes.restype = C.c_size_t
+    lib.rocket_train_step.argtypes = [vp, vp, C.c_int, i32, u32, f32, f32, vp, vp, vp, f32, C.c_int, vp, vp,
+                                      C.c_size_t, vp]
+    lib.rocket_kernels_subset.argtypes = [vp, vp, i32, C.POINTER(vp)]
     lib.rocket_free_kernels.argtypes = [vp]
     lib.rocket_free_kernels.restype = None
     lib.rocket_last_error.restype = C.c_char_p
@@ -332,6 +341,75 @@ def rocket_infer(kernels, x, feature_mask, coef, intercept, lam=10.0, shift=-3.0
         coef.data_ptr(), intercept.data_ptr(), features.data_ptr(), pred.data_ptr(),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(torch, stream)))
     return pred, features
+
+
+def rocket_mse_grad(pred, targets, coef, grad_out=None, stream=None):
+    """pred float64 (B,), targets float32 (B,), coef float64 (p,), all CUDA.
+    Returns (grad_out float32 (B, p), loss float64 (1,))."""
+    torch = _torch()
+    B, p = pred.numel(), coef.numel()
+    if not (pred.is_cuda and pred.dtype == torch.float64 and targets.is_cuda and targets.dtype == torch.float32
+            and targets.numel() == B and coef.is_cuda and coef.dtype == torch.float64
+            and pred.is_contiguous() and targets.is_contiguous() and coef.is_contiguous()):
+        raise RocketError(ROCKET_EINVAL, "pred float64 (B,), targets float32 (B,), coef float64 (p,) CUDA tensors expected")
+    if grad_out is None:
+        grad_out = torch.empty((B, p), dtype=torch.float32, device=pred.device)
+    loss = torch.empty(1, dtype=torch.float64, device=pred.device)
+    _check(load_library().rocket_mse_grad(pred.data_ptr(), targets.data_ptr(), coef.data_ptr(), B, p,
+                                          grad_out.data_ptr(), loss.data_ptr(), _stream_ptr(torch, stream)))
+    return grad_out, loss
+
+
+def rocket_sgd_update(kernels, grad_w, grad_b, lr, recentre=False, stream=None):
+    torch = _torch()
+    v = _View()
+    _check(load_library().rocket_kernels_view_get(kernels.handle, C.byref(v)))
+    for t, n, name in ((grad_w, v.total_weights, "grad_w"), (grad_b, v.K, "grad_b")):
+        if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == n):
+            raise RocketError(ROCKET_EINVAL, "%s must be a contiguous float32 CUDA tensor of %d elements" % (name, n))
+    _check(load_library().rocket_sgd_update(kernels.handle, grad_w.data_ptr(), grad_b.data_ptr(), lr,
+                                            int(bool(recentre)), _stream_ptr(torch, stream)))
+
+
+def rocket_train_workspace_bytes(kernels, B, feature_mask):
+    return int(load_library().rocket_train_workspace_bytes(kernels.handle, B, feature_mask))
+
+
+def rocket_train_step(kernels, x, feature_mask, coef, intercept, targets, lr, lam=10.0, shift=-3.0, recentre=False,
+                      workspace=None, stream=None):
+    """One gradient-descent step on the kernels' weights and biases.  Returns the loss before
+    the update as a float64 CUDA tensor of one element."""
+    torch = _torch()
+    if not (x.is_cuda and x.dtype in (torch.float32, torch.uint8) and x.is_contiguous() and x.dim() == 3):
+        raise RocketError(ROCKET_EINVAL, "x must be a contiguous float32 or uint8 CUDA tensor of shape (B, C, L)")
+    v = _View()
+    _check(load_library().rocket_kernels_view_get(kernels.handle, C.byref(v)))
+    B = x.shape[0]
+    if x.shape[1] != v.C or x.shape[2] != v.L:
+        raise RocketError(ROCKET_ESHAPE, "x does not match the kernels' (C, L)")
+    p = rocket_num_features(feature_mask) * v.K
+    if not (coef.is_cuda and coef.dtype == torch.float64 and coef.numel() == p and coef.is_contiguous()
+            and intercept.is_cuda and intercept.dtype == torch.float64 and intercept.numel() == 1
+            and targets.is_cuda and targets.dtype == torch.float32 and targets.numel() == B
+            and targets.is_contiguous()):
+        raise RocketError(ROCKET_EINVAL, "coef float64 (F*K,), intercept float64 (1,), targets float32 (B,) CUDA expected")
+    if workspace is None:
+        workspace = torch.empty(rocket_train_workspace_bytes(kernels, B, feature_mask), dtype=torch.uint8,
+                                device=x.device)
+    loss = torch.empty(1, dtype=torch.float64, device=x.device)
+    _check(load_library().rocket_train_step(
+        kernels.handle, x.data_ptr(), int(x.dtype == torch.uint8), B, feature_mask, lam, shift,
+        coef.data_ptr(), intercept.data_ptr(), targets.data_ptr(), lr, int(bool(recentre)), loss.data_ptr(),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(torch, stream)))
+    return loss
+
+
+def rocket_kernels_subset(kernels, index):
+    idx = np.ascontiguousarray(index, dtype=np.int32)
+    out = C.c_void_p()
+    _check(load_library().rocket_kernels_subset(kernels.handle, idx.ctypes.data_as(C.c_void_p), len(idx),
+                                                C.byref(out)))
+    return Kernels(out.value)
 
 
 def rocket_free_kernels(kernels):

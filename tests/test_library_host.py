@@ -115,3 +115,20 @@ def test_argument_validation_without_gpu():
     assert lib.rocket_soft_ppv_backward(h.handle, dummy, 1, 4, dummy, 10.0, -3.0, 1, dummy, dummy, dummy, 1 << 30, None) == rocket.ROCKET_EINVAL
     h.free()
     rocket.load_library().rocket_free_kernels(None)
+
+
+def test_subset_keeps_the_chosen_kernels():
+    """host-only: rocket_kernels_subset copies the selected kernels, in the given order"""
+    h = rocket.rocket_make_kernels(3, 50, 6, 900)
+    kr = rocket.rocket_kernels_view_get(h)
+    idx = np.array([7, 0, 49, 7], np.int32)
+    hs = rocket.rocket_kernels_subset(h, idx)
+    ks = rocket.rocket_kernels_view_get(hs)
+    assert len(ks["length"]) == 4
+    for i, k in enumerate(idx):
+        for name in ("length", "dilation", "padding", "n_ch", "bias"):
+            assert ks[name][i] == kr[name][k]
+        assert np.array_equal(ks["weights"][ks["w_off"][i]:ks["w_off"][i + 1]], kr["weights"][kr["w_off"][k]:kr["w_off"][k + 1]])
+        assert np.array_equal(ks["channels"][ks["ch_off"][i]:ks["ch_off"][i + 1]], kr["channels"][kr["ch_off"][k]:kr["ch_off"][k + 1]])
+    with pytest.raises(rocket.RocketError):
+        rocket.rocket_kernels_subset(h, np.array([50], np.int32))
