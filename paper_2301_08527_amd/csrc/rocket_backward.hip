@@ -131,6 +131,97 @@ __device__ __forceinline__ void rk_bwd_segment(const KernelCtx &k, int row0, int
     }
 }
 
+// One band of R < 32 rows.  A lane takes S column blocks (columns tid, tid + 256, ...) per pass,
+// so that R*S outputs share one cross-lane reduction per weight: with few rows per band the
+// reduction, not the multiply-adds, would otherwise dominate (a kernel with dilation in the
+// thousands has a dozen rows in all).  Column blocks that lie wholly beyond the band for this
+// wavefront are skipped by wavefront-uniform branches.
+template <int LEN, int R, int S>
+__device__ __forceinline__ void rk_bwd_band(const KernelCtx &k, int row0, int ncols, float coef, bool want_max,
+                                            float *slots, BwdState &st)
+{
+    const uint32_t dbytes = static_cast<uint32_t>(k.d) * 4u;
+    const int tid = static_cast<int>(threadIdx.x);
+    const int wave0 = __builtin_amdgcn_readfirstlane(tid & ~63);    // first lane of this wavefront
+    for (int base = 0; base < ncols; base += S * kThreads) {        // uniform trip count
+        if (base + wave0 >= ncols) continue;                        // nothing for this wavefront in this pass
+        float acc[S][R];
+        uint32_t voff[S];
+        int t0[S];
+        float lane_coef[S];
+        bool live[S];
+        rk_static_for<0, S>([&](auto sc) {
+            constexpr int s = decltype(sc)::value;
+            const int col = base + s * kThreads + tid;
+            const bool valid = col < ncols;
+            live[s] = base + s * kThreads + wave0 < ncols;          // wavefront-uniform
+            lane_coef[s] = valid ? coef : 0.f;
+            t0[s] = row0 * k.d + (valid ? col : ncols - 1);         // idle lanes redo the last column with weight 0
+            voff[s] = static_cast<uint32_t>(t0[s]) * 4u;
+#pragma unroll
+            for (int i = 0; i < R; ++i) acc[s][i] = 0.f;
+        });
+        for (int c = 0; c < k.nch; ++c) {
+            const __amdgpu_buffer_rsrc_t row =
+                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+            float w[LEN];
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
+            rk_static_for<0, S>([&](auto sc) {
+                constexpr int s = decltype(sc)::value;
+                if (live[s]) {
+                    uint32_t soff = 0;
+                    rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                        constexpr int i = decltype(ic)::value;
+                        rk_taps<LEN, R, i>(w, rk_load(row, voff[s], soff), acc[s]);
+                        soff = rk_advance(soff, dbytes);
+                    });
+                }
+            });
+        }
+        rk_static_for<0, S>([&](auto sc) {
+            constexpr int s = decltype(sc)::value;
+            if (live[s]) {
+                if (want_max) {
+#pragma unroll
+                    for (int i = 0; i < R; ++i) {
+                        if (acc[s][i] > st.vmax) { st.vmax = acc[s][i]; st.targ = t0[s] + i * k.d; }
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < R; ++i) {
+                    acc[s][i] = lane_coef[s] * rk_dsigmoid(acc[s][i], k.nl, k.ns);   // acc now holds q
+                    st.qsum += acc[s][i];
+                }
+            }
+        });
+        for (int c = 0; c < k.nch; ++c) {
+            const __amdgpu_buffer_rsrc_t row =
+                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+            float g[LEN];
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) g[j] = 0.f;
+            rk_static_for<0, S>([&](auto sc) {
+                constexpr int s = decltype(sc)::value;
+                if (live[s]) {
+                    uint32_t soff = 0;
+                    rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                        constexpr int i = decltype(ic)::value;
+                        const float xv = rk_load(row, voff[s], soff);
+                        soff = rk_advance(soff, dbytes);
+                        rk_static_for<0, LEN>([&](auto jc) {
+                            constexpr int j = decltype(jc)::value;
+                            constexpr int o = i - j;
+                            if constexpr (o >= 0 && o < R) g[j] = fmaf(acc[s][o], xv, g[j]);
+                        });
+                    });
+                }
+            });
+            rk_bwd_deposit<LEN>(g, c, slots);
+        }
+    }
+}
+
 // LDS path of the backward pass (d < 8): the chunk's input range is staged once per
 // channel for the conv and once more for the weight gradient.
 template <int LEN, int D>
@@ -227,12 +318,12 @@ __device__ __forceinline__ void rk_backward_body(const KernelCtx &k, int nout, f
     const int rows = total_rows - row0;   // rows left for the register path
     const int nb32 = rows >> 5;
     if (nb32) { rk_bwd_segment<LEN, 32>(k, row0, nb32, d, coef, want_max, slots, st); row0 += nb32 << 5; }
-    if (rows & 16) { rk_bwd_segment<LEN, 16>(k, row0, 1, d, coef, want_max, slots, st); row0 += 16; }
-    if (rows & 8) { rk_bwd_segment<LEN, 8>(k, row0, 1, d, coef, want_max, slots, st); row0 += 8; }
-    if (rows & 4) { rk_bwd_segment<LEN, 4>(k, row0, 1, d, coef, want_max, slots, st); row0 += 4; }
-    if (rows & 2) { rk_bwd_segment<LEN, 2>(k, row0, 1, d, coef, want_max, slots, st); row0 += 2; }
-    if (rows & 1) { rk_bwd_segment<LEN, 1>(k, row0, 1, d, coef, want_max, slots, st); row0 += 1; }
-    if (tail) rk_bwd_segment<LEN, 1>(k, row0, 1, tail, coef, want_max, slots, st);
+    if (rows & 16) { rk_bwd_band<LEN, 16, 2>(k, row0, d, coef, want_max, slots, st); row0 += 16; }
+    if (rows & 8) { rk_bwd_band<LEN, 8, 4>(k, row0, d, coef, want_max, slots, st); row0 += 8; }
+    if (rows & 4) { rk_bwd_band<LEN, 4, 8>(k, row0, d, coef, want_max, slots, st); row0 += 4; }
+    if (rows & 2) { rk_bwd_band<LEN, 2, 8>(k, row0, d, coef, want_max, slots, st); row0 += 2; }
+    if (rows & 1) { rk_bwd_band<LEN, 1, 8>(k, row0, d, coef, want_max, slots, st); row0 += 1; }
+    if (tail) rk_bwd_band<LEN, 1, 8>(k, row0, tail, coef, want_max, slots, st);
 }
 
 // grid: B*K workgroups.  grad_out is B x (F*K); plane_soft / plane_max are the plane
