@@ -196,3 +196,24 @@ def test_shape_mismatch_is_an_error():
         rocket.rocket_transform(h, _gpu(np.zeros((2, 1, 500), np.float32)), 3)
     with pytest.raises(rocket.RocketError):
         rocket.rocket_transform(h, _gpu(np.zeros((2, 2, 512), np.float32)), 3)
+
+
+def test_very_long_series_forward_and_backward():
+    """one series of 3,000,000 samples: dilations up to ~375,000 (a dozen rows of that many columns),
+    padding up to ~1.5 M zeros on either side, ~180 time tiles per kernel"""
+    import torch
+    L, C, K = 3_000_000, 2, 32
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((1, C, L)).astype(np.float32)
+    h = rocket.rocket_make_kernels(7, K, C, L)
+    kr = rocket.rocket_kernels_view_get(h)
+    assert kr["dilation"].max() > 100_000
+    print("3M-sample forward", flush=True)
+    out = _run(h, x, 7)
+    check_forward(x, kr, out, 7)
+    from parity import check_backward
+    g = rng.standard_normal((1, 3 * K)).astype(np.float32)
+    print("3M-sample backward", flush=True)
+    gw, gb = rocket.rocket_soft_ppv_backward(h, _gpu(x), 7, _gpu(g), 10.0, -3.0, False)
+    torch.cuda.synchronize()
+    check_backward(x, kr, gw.cpu().numpy(), gb.cpu().numpy(), g[:, 2 * K:], None, 10.0, -3.0)
