@@ -13,6 +13,8 @@ import os
 import sys
 import time
 
+import numpy as np
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
@@ -60,6 +62,28 @@ def cpu_baseline(cfg_id, x_host, kr, mask, lam, n_examples):
         "sample": "%d example(s) x all %d kernels of the same workload, %.1f s, fp64, all features at once"
                   % (n_examples, len(kr["length"]), dt),
     }
+
+
+def quick_rate(rocket, synth, torch, cfg_id, lam, steps=20, warmup=3):
+    """series/s and conv TFLOP/s of a small workload, whole batch resident, same timing rules."""
+    cfg = synth.CONFIGS[cfg_id]
+    B, mask = cfg["B"], cfg["features"]
+    h = rocket.rocket_make_kernels(synth.seed_k(cfg_id), cfg["K"], cfg["C"], cfg["L"])
+    fma, _ = rocket.rocket_work_per_series(h)
+    x = torch.from_numpy(synth.make_input(cfg_id)).cuda()
+    out = torch.empty((B, rocket.rocket_num_features(mask) * cfg["K"]), dtype=torch.float32, device="cuda")
+    ws = torch.empty(rocket.rocket_workspace_bytes(h, B, mask), dtype=torch.uint8, device="cuda")
+    for _ in range(warmup):
+        rocket.rocket_transform(h, x, mask, lam, -3.0, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        rocket.rocket_transform(h, x, mask, lam, -3.0, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    h.free()
+    return {"workload": cfg["name"], "B": B, "C": cfg["C"], "L": cfg["L"], "K": cfg["K"], "features": mask,
+            "value": B / dt, "unit": "series/s", "ms_per_step": 1e3 * dt, "conv_tflops": 2.0 * fma * B / dt / 1e12}
 
 
 def main():
@@ -185,6 +209,12 @@ def main():
         },
         "percent_of_fp32_vector_peak": 100.0 * achieved / FP32_VECTOR_PEAK_TFLOPS,
     }
+
+    if traffic:
+        line["roofline"]["hbm_GBps"] = traffic / (kernel_ms_avg * 1e-3) / 1e9
+    if cfg_id == 2 and not from_u8:
+        # the univariate workloads of the classic ROCKET setting, in series/s, in the same run
+        line["series_per_s"] = [quick_rate(rocket, synth, torch, i, args.lam) for i in (1, 0)]
 
     if not args.no_cpu_baseline and not with_grad:
         kr = rocket.rocket_kernels_view_get(h)
