@@ -124,7 +124,9 @@ size_t rocket_workspace_bytes(const rocket_kernels *kernels, int32_t B, uint32_t
  * rocket_workspace_bytes(kernels, B, mask, 0) bytes, 256-byte aligned.
  * lambda and shift are used by ROCKET_F_SOFTPPV only (the paper's reading is
  * shift = -3).  On first use the handle uploads its parameters to the current
- * device (one hipMalloc); later calls allocate nothing.
+ * device (one hipMalloc); later calls allocate nothing, copy nothing and never
+ * synchronise: they only launch kernels on hip_stream, so they can be recorded
+ * by a stream capture (while rocket_profile_enable is off).
  */
 int rocket_transform(rocket_kernels *kernels, const float *x_dev, int32_t B, uint32_t feature_mask,
                      float lambda, float shift, float *out_dev,

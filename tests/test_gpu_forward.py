@@ -217,3 +217,37 @@ def test_very_long_series_forward_and_backward():
     gw, gb = rocket.rocket_soft_ppv_backward(h, _gpu(x), 7, _gpu(g), 10.0, -3.0, False)
     torch.cuda.synchronize()
     check_backward(x, kr, gw.cpu().numpy(), gb.cpu().numpy(), g[:, 2 * K:], None, 10.0, -3.0)
+
+
+def test_transform_can_be_captured_in_a_graph():
+    """After the first call on a handle the transform only launches kernels (no allocation, no
+    copy, no synchronisation), so a stream capture records it; every replay must give the
+    eager result for the input that is in the captured buffer at that time."""
+    import torch
+    cfg = synth.CONFIGS[0]
+    h, kr = _kernels(0)
+    mask = 7
+    xs = [synth.make_input(0), synth.make_input(0)[::-1].copy(), 0.5 * synth.make_input(0)]
+    x = _gpu(xs[0])
+    out = torch.empty((cfg["B"], 3 * cfg["K"]), dtype=torch.float32, device="cuda")
+    ws = torch.empty(rocket.rocket_workspace_bytes(h, cfg["B"], mask), dtype=torch.uint8, device="cuda")
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        rocket.rocket_transform(h, x, mask, out=out, workspace=ws)       # first use: uploads the parameters
+    s.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    print("capturing", flush=True)
+    with torch.cuda.graph(graph, stream=s):
+        rocket.rocket_transform(h, x, mask, out=out, workspace=ws)
+    for i, xi in enumerate(xs):
+        x.copy_(_gpu(xi))
+        out.fill_(-1.0)
+        torch.cuda.synchronize()
+        print("replay", i, flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().copy()
+        eager = rocket.rocket_transform(h, x, mask)
+        torch.cuda.synchronize()
+        assert np.array_equal(got, eager.cpu().numpy())
+        check_forward(xi, kr, got, mask)
