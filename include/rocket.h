@@ -193,6 +193,15 @@ int rocket_profile_enable(rocket_kernels *kernels, int enable);
 int rocket_profile_read(rocket_kernels *kernels, int32_t *launches, double *total_ms);
 
 /*
+ * Measured ceiling for the roofline figure: runs a kernel that issues nothing but plain
+ * (one per lane) FP32 fused multiply-adds from every vector ALU of the current device, waits
+ * for it, and returns its rate in *tflops (host pointer).  The transform's arithmetic is made
+ * of the same instruction; the data-sheet FP32 vector peak assumes the packed form and is
+ * twice this.  Takes a few milliseconds; allocates and frees a few bytes and two events.
+ */
+int rocket_calibrate_fma(double *tflops, void *hip_stream);
+
+/*
  * Ridge regressor on the pooled features (paper section 3 part (3), section 3.3):
  * minimises ||y - X w - b||^2 + alpha ||w||^2 over (w, b), the intercept b unpenalised.
  * features_dev: device, n x p float32 row-major (the transform's output for n series);

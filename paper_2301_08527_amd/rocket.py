@@ -22,7 +22,7 @@ EXPORTS = [
     "rocket_kernels_set_params", "rocket_num_features", "rocket_workspace_bytes",
     "rocket_transform", "rocket_soft_ppv_backward", "rocket_transform_u8", "rocket_soft_ppv_backward_u8",
     "rocket_work_per_series",
-    "rocket_profile_enable", "rocket_profile_read",
+    "rocket_profile_enable", "rocket_profile_read", "rocket_calibrate_fma",
     "rocket_ridge_workspace_bytes", "rocket_ridge_fit", "rocket_ridge_predict", "rocket_infer",
     "rocket_mse_grad", "rocket_sgd_update", "rocket_train_workspace_bytes", "rocket_train_step",
     "rocket_kernels_subset",
@@ -76,6 +76,7 @@ def load_library():
     lib.rocket_work_per_series.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.rocket_profile_enable.argtypes = [vp, C.c_int]
     lib.rocket_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]
+    lib.rocket_calibrate_fma.argtypes = [C.POINTER(C.c_double), vp]
     lib.rocket_ridge_workspace_bytes.argtypes = [i32, i32]
     lib.rocket_ridge_workspace_bytes.restype = C.c_size_t
     lib.rocket_ridge_fit.argtypes = [vp, vp, i32, i32, C.c_double, vp, vp, vp, C.c_size_t, vp]
@@ -279,6 +280,14 @@ def rocket_soft_ppv_backward_u8(kernels, x_u8, feature_mask, grad_out, lam=10.0,
     return rocket_soft_ppv_backward(kernels, x_u8, feature_mask, grad_out, lam, shift, include_max,
                                     grad_w, grad_b, workspace, stream,
                                     _dtype="uint8", _entry="rocket_soft_ppv_backward_u8")
+
+
+def rocket_calibrate_fma(stream=None):
+    """Measured plain-FMA rate of the current device in TFLOP/s."""
+    torch = _torch()
+    v = C.c_double()
+    _check(load_library().rocket_calibrate_fma(C.byref(v), _stream_ptr(torch, stream)))
+    return v.value
 
 
 def rocket_ridge_workspace_bytes(n, p):
