@@ -34,28 +34,65 @@ MUTATIONS = [
 ]
 
 
+# (name, oracle file, pin file, text, replacement): mistakes in the Python parts of the oracle
+PY_MUTATIONS = [
+    ("z-score with the sample std", "prologue.py", "test_oracle_prologue.py",
+     "std = np.sqrt(((v - mean) ** 2).mean(axis=-1, keepdims=True))",
+     "std = np.sqrt(((v - mean) ** 2).sum(axis=-1, keepdims=True) / (v.shape[-1] - 1))"),
+    ("z-score without centring", "prologue.py", "test_oracle_prologue.py",
+     "z = np.where(std > 0, (v - mean) / np.where(std > 0, std, 1.0), 0.0)",
+     "z = np.where(std > 0, v / np.where(std > 0, std, 1.0), 0.0)"),
+    ("constant row not zeroed", "prologue.py", "test_oracle_prologue.py",
+     "z = np.where(std > 0, (v - mean) / np.where(std > 0, std, 1.0), 0.0)",
+     "z = (v - mean) / np.where(std > 0, std, 1.0) + (std == 0)"),
+    ("ridge intercept penalised", "ridge.py", "test_oracle_ridge.py",
+     "return w, y_mean - x_mean @ w", "return w, (y_mean - x_mean @ w) / (1.0 + alpha / n)"),
+    ("ridge penalty dropped in the dual branch", "ridge.py", "test_oracle_ridge.py",
+     "Xc @ Xc.T + alpha * np.eye(n)", "Xc @ Xc.T + 1e-9 * np.eye(n)"),
+    ("ridge columns not centred", "ridge.py", "test_oracle_ridge.py", "Xc = X - x_mean", "Xc = X"),
+    ("ridge penalty squared", "ridge.py", "test_oracle_ridge.py",
+     "Xc.T @ Xc + alpha * np.eye(p)", "Xc.T @ Xc + alpha * alpha * np.eye(p)"),
+    ("loss gradient without 2/B", "train.py", "test_oracle_train.py",
+     "(2.0 / len(y)) * r[:, None] * coef[None, :]", "r[:, None] * coef[None, :]"),
+    ("update with the wrong sign", "train.py", "test_oracle_train.py",
+     "np.asarray(kr[\"weights\"], np.float64) - float(lr)", "np.asarray(kr[\"weights\"], np.float64) + float(lr)"),
+    ("bias not updated", "train.py", "test_oracle_train.py",
+     "b = np.asarray(kr[\"bias\"], np.float64) - float(lr) * np.asarray(gb, np.float64)",
+     "b = np.asarray(kr[\"bias\"], np.float64)"),
+    ("re-centring over the whole kernel", "train.py", "test_oracle_train.py",
+     "                row = w[lo + c * ln: lo + (c + 1) * ln]\n                row -= row.mean()",
+     "                row = w[lo + c * ln: lo + (c + 1) * ln]\n                row -= w[lo: lo + ln * int(kr[\"n_ch\"][k])].mean()"),
+    ("max plane left out of the step", "train.py", "test_oracle_train.py",
+     "g_max = G[:, :K] if mask & 1 else None", "g_max = None"),
+    ("soft plane taken from the wrong columns", "train.py", "test_oracle_train.py",
+     "g_soft = G[:, (planes - 1) * K:]", "g_soft = G[:, :K]"),
+]
+
+
 @pytest.fixture(scope="module")
 def clean_copy(tmp_path_factory):
     base = tmp_path_factory.mktemp("oracle_mutants")
     return str(base)
 
 
-def _run_pins(workdir):
+def _run_pins(workdir, pin_file="test_oracle_pins.py"):
     env = dict(os.environ, PYTHONPATH=workdir + os.pathsep + ROOT)
-    tests = [os.path.join(ROOT, "tests", "test_oracle_pins.py")]
+    tests = [os.path.join(ROOT, "tests", pin_file)]
     return subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
                            "--rootdir", workdir, "-c", os.devnull] + tests,
                           env=env, cwd=workdir, capture_output=True, text=True, timeout=600)
 
 
-def _make_copy(workdir, name, old=None, new=None):
+def _make_copy(workdir, name, old=None, new=None, target="rocket_oracle.c"):
     d = os.path.join(workdir, name)
     os.makedirs(d)
     pkg = os.path.join(d, "oracle")
-    shutil.copytree(os.path.join(ROOT, "oracle"), pkg, ignore=shutil.ignore_patterns("*.so", "__pycache__"))
+    # a mutant of the C file must rebuild its library; the others can take the built one along
+    skip = ("*.so", "__pycache__") if target.endswith(".c") else ("__pycache__",)
+    shutil.copytree(os.path.join(ROOT, "oracle"), pkg, ignore=shutil.ignore_patterns(*skip))
     shutil.copy(os.path.join(ROOT, "tests", "conftest.py"), os.path.join(d, "conftest.py"))
     if old is not None:
-        path = os.path.join(pkg, "rocket_oracle.c")
+        path = os.path.join(pkg, target)
         src = open(path).read()
         assert src.count(old) >= 1, "mutation target not found: " + old[:40]
         open(path, "w").write(src.replace(old, new, 1))
@@ -73,4 +110,12 @@ def test_planted_mistake_is_caught(clean_copy, idx):
     r = _run_pins(_make_copy(clean_copy, "m%d" % idx, old, new))
     assert r.returncode != 0, "pins did not notice: " + name
     # it must be a failing pin, not a mutant that does not compile or import
+    assert " failed" in r.stdout and "CalledProcessError" not in r.stdout and "ImportError" not in r.stdout, r.stdout[-800:]
+
+
+@pytest.mark.parametrize("idx", range(len(PY_MUTATIONS)), ids=[m[0] for m in PY_MUTATIONS])
+def test_planted_mistake_in_the_python_parts_is_caught(clean_copy, idx):
+    name, target, pin_file, old, new = PY_MUTATIONS[idx]
+    r = _run_pins(_make_copy(clean_copy, "p%d" % idx, old, new, target), pin_file)
+    assert r.returncode != 0, "pins did not notice: " + name
     assert " failed" in r.stdout and "CalledProcessError" not in r.stdout and "ImportError" not in r.stdout, r.stdout[-800:]
