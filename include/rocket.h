@@ -254,7 +254,9 @@ int rocket_infer(rocket_kernels *kernels, const void *x_dev, int x_is_u8, int32_
  * its mean subtracted, which keeps the sampler's invariant of section 3.1.  Nothing is copied
  * to the host: later transforms on the handle use the new parameters, and the next
  * rocket_kernels_view_get (or rocket_kernels_set_params, rocket_kernels_subset) first waits for
- * the stream of the last update and downloads them.
+ * the device to finish and downloads them.  Updates and transforms of one handle are ordered
+ * by the stream they share; an update on a different stream than the previous one first waits
+ * for the device.
  *
  * rocket_train_step: transform (feature_mask must contain ROCKET_F_SOFTPPV; the max plane, when
  * present, sends its sub-gradient to its first arg-max, the PPV plane none), prediction, loss

@@ -245,7 +245,8 @@ static int download_params(rocket_kernels *h)
     RK_HIP(hipGetDevice(&cur));
     if (cur != h->device) RK_HIP(hipSetDevice(h->device));
     std::vector<RkKernelRec> rec(h->K);
-    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(h->update_stream));
+    // the stream of the update may no longer exist: wait for the whole device
+    hipError_t e = hipDeviceSynchronize();
     if (e == hipSuccess) e = hipMemcpy(h->weights.data(), h->d_weights, h->weights.size() * 4, hipMemcpyDeviceToHost);
     if (e == hipSuccess) e = hipMemcpy(rec.data(), h->d_rec, rec.size() * sizeof(RkKernelRec), hipMemcpyDeviceToHost);
     if (cur != h->device) (void)hipSetDevice(cur);
@@ -602,8 +603,8 @@ extern "C" int rocket_sgd_update(rocket_kernels *h, const float *grad_w_dev, con
     int rc = ensure_device(h, stream);      // uploads host-side parameters first if they are the newer ones
     if (rc != ROCKET_OK) return rc;
     if (h->host_stale && h->update_stream != hip_stream) {
-        // an earlier update ran on another stream: order this one after it
-        RK_HIP(hipStreamSynchronize(static_cast<hipStream_t>(h->update_stream)));
+        // an earlier update ran on another stream (which may no longer exist): order this one after it
+        RK_HIP(hipDeviceSynchronize());
     }
     if (rk_launch_sgd_update(h, grad_w_dev, grad_b_dev, lr, recentre, stream) != ROCKET_OK)
         return rk_fail(ROCKET_EHIP, "launch of the update kernel failed");
