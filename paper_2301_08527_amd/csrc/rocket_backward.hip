@@ -27,15 +27,15 @@ struct BwdState {
     int targ;       // per lane: first position attaining vmax
 };
 
-// softPPV derivative factor: given z = y - bias returns s(1-s) with
-// s = 1/(1+e), e = exp(-(lambda*y+shift)) = exp2(z*nl + ns).  The exponent is capped so
-// that e stays finite; 1-s is formed as e*s, which keeps its relative accuracy
-// when s is close to 1.
-__device__ __forceinline__ float rk_dsigmoid(float z, float nl, float ns)
+// q = coef * s(1-s) for z = y - bias, with s = 1/(1+e), e = exp(-(lambda*y+shift)) = exp2(t),
+// t = z*nl + ns.  s(1-s) is even in t, so it is evaluated at -|t|: e <= 1 never overflows (no cap
+// on the exponent is needed, and the sign flip is a free source modifier), and 1-s is formed as
+// e*s, which keeps its relative accuracy in the saturated tails where s - s*s would cancel.
+__device__ __forceinline__ float rk_q(float z, float coef, float nl, float ns)
 {
-    const float e = __builtin_amdgcn_exp2f(fminf(fmaf(z, nl, ns), 80.f));
+    const float e = __builtin_amdgcn_exp2f(-fabsf(fmaf(z, nl, ns)));
     const float sg = __builtin_amdgcn_rcpf(1.f + e);
-    return sg * (e * sg);
+    return coef * sg * (e * sg);
 }
 
 // Sum over each row of 16 lanes (all 16 lanes end up with the row sum).
@@ -106,7 +106,7 @@ __device__ __forceinline__ void rk_bwd_segment(const KernelCtx &k, int row0, int
         }
 #pragma unroll
         for (int i = 0; i < R; ++i) {
-            acc[i] = lane_coef * rk_dsigmoid(acc[i], k.nl, k.ns);   // acc now holds q
+            acc[i] = rk_q(acc[i], lane_coef, k.nl, k.ns);   // acc now holds q
             st.qsum += acc[i];
         }
         for (int c = 0; c < k.nch; ++c) {
@@ -190,7 +190,7 @@ __device__ __forceinline__ void rk_bwd_band(const KernelCtx &k, int row0, int nc
                 }
 #pragma unroll
                 for (int i = 0; i < R; ++i) {
-                    acc[s][i] = lane_coef[s] * rk_dsigmoid(acc[s][i], k.nl, k.ns);   // acc now holds q
+                    acc[s][i] = rk_q(acc[s][i], lane_coef[s], k.nl, k.ns);   // acc now holds q
                     st.qsum += acc[s][i];
                 }
             }
@@ -268,7 +268,7 @@ __device__ __forceinline__ int rk_bwd_lds_bands(const KernelCtx &k, int rows, fl
             }
 #pragma unroll
             for (int i = 0; i < R; ++i) {
-                acc[i] = lane_coef * rk_dsigmoid(acc[i], k.nl, k.ns);
+                acc[i] = rk_q(acc[i], lane_coef, k.nl, k.ns);
                 st.qsum += acc[i];
             }
         }
