@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--features", type=int, default=None, help="feature mask override (1=max, 2=PPV, 4=softPPV)")
     ap.add_argument("--lam", type=float, default=10.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--lean", action="store_true",
+                    help="only the timed region: no extra workloads, no H2D-inclusive run, no FMA calibration "
+                         "(for profiler runs, so that the trace holds the timed launches only)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time its replays (for launch-bound small workloads)")
     ap.add_argument("--cpu-examples", type=int, default=None, help="examples in the oracle's timed sample")
@@ -205,7 +208,7 @@ def main():
     pool_per_pos = (1 if mask & 1 else 0) + (2 if mask & 2 else 0) + (6 if mask & 4 else 0)
     pool_flops = outputs_per_series * B * (10.0 if with_grad else pool_per_pos)
     achieved_with_pooling = (flops_per_launch + pool_flops) / (kernel_ms_avg * 1e-3) / 1e12
-    plain_fma_ceiling = rocket.rocket_calibrate_fma()
+    plain_fma_ceiling = None if args.lean else rocket.rocket_calibrate_fma()
     traffic = None
     if os.path.exists(TRAFFIC_FILE):
         try:
@@ -233,7 +236,8 @@ def main():
             "flop_per_launch": flops_per_launch, "fma_per_example": fma_per_series,
             "pooled_positions_per_example": outputs_per_series,
             "achieved_with_pooling": achieved_with_pooling,
-            "plain_fma_measured": plain_fma_ceiling, "frac_of_plain_fma_measured": achieved / plain_fma_ceiling,
+            "plain_fma_measured": plain_fma_ceiling,
+            "frac_of_plain_fma_measured": achieved / plain_fma_ceiling if plain_fma_ceiling else None,
             "note": "peak is the data-sheet figure, which assumes packed FP32; this build issues plain v_fma_f32, "
                     "whose rate measured in this run by a kernel of nothing but FMAs is plain_fma_measured",
         },
@@ -242,11 +246,11 @@ def main():
 
     if traffic:
         line["roofline"]["hbm_GBps"] = traffic / (kernel_ms_avg * 1e-3) / 1e9
-    if cfg_id == 2 and not from_u8:
+    if cfg_id == 2 and not from_u8 and not args.lean:
         # the univariate workloads of the classic ROCKET setting, in series/s, in the same run
         line["series_per_s"] = [quick_rate(rocket, synth, torch, i, args.lam) for i in (1, 0)]
 
-    if cfg_id == 2 and not train:
+    if cfg_id == 2 and not train and not args.lean:
         # once with the host-to-device copy of the batch inside the timed region (pinned source)
         x_pin = torch.from_numpy(x_host).pin_memory()
         for _ in range(2):

@@ -455,7 +455,7 @@ static int check_common(const char *fn, const rocket_kernels *h, const void *x, 
     if (B < 1) return rk_fail(ROCKET_EINVAL, who + ": B must be >= 1");
     if (rocket_num_features(mask) == 0) return rk_fail(ROCKET_EINVAL, who + ": feature mask must be a non-empty subset of 7");
     if (!std::isfinite(lambda) || !std::isfinite(shift)) return rk_fail(ROCKET_EINVAL, who + ": lambda and shift must be finite");
-    if (static_cast<int64_t>(B) * static_cast<int64_t>(std::max<size_t>(h->jobs.size(), h->K)) > INT32_MAX)
+    if (rk_grid_groups(B, static_cast<int64_t>(std::max<size_t>(h->jobs.size(), h->K)), 1) > INT32_MAX)
         return rk_fail(ROCKET_EINVAL, who + ": B times the number of work items exceeds the grid limit");
     const size_t need = rocket_workspace_bytes(h, B, mask, backward);
     if (!ws || ws_bytes < need)

@@ -326,7 +326,7 @@ __device__ __forceinline__ void rk_backward_body(const KernelCtx &k, int nout, f
     if (tail) rk_bwd_band<LEN, 1, 8>(k, row0, tail, coef, want_max, slots, st);
 }
 
-// grid: B*K workgroups.  grad_out is B x (F*K); plane_soft / plane_max are the plane
+// grid: one workgroup per (series, kernel), mapped by rk_block_to_pair.  grad_out is B x (F*K); plane_soft / plane_max are the plane
 // indices of the softPPV and max features in it (plane_max < 0: max not included).
 // partial is B rows of (total_w + K) floats: weight gradients in the layout of
 // `weights`, then the K bias gradients.
@@ -337,15 +337,16 @@ __global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict_
                                                         const float *__restrict__ weights,
                                                         const float *__restrict__ grad_out, int F, int plane_soft,
                                                         int plane_max, float lambda, float nl, float ns,
-                                                        float *__restrict__ partial, int total_w)
+                                                        float *__restrict__ partial, int total_w, int B, int spread)
 {
     __shared__ float tile[kLdsTileWords];
     __shared__ float slots[kBwdMaxTerms * kBwdSlots];
     __shared__ float s_q[kWaves];
     __shared__ float s_max[kWaves];
     __shared__ int s_arg[kWaves];
-    const int b = blockIdx.x / K;
-    const int kid = order[blockIdx.x - b * K];
+    int b, item;
+    if (!rk_block_to_pair(K, B, spread, b, item)) return;
+    const int kid = order[item];
     const RkKernelRec rec = recs[kid];
     KernelCtx k = rk_make_ctx(rec, xpad, row_len, lead, L, C, b, channels, weights);
     k.nl = nl;
@@ -427,9 +428,9 @@ int rk_launch_backward(const rocket_kernels *h, const float *xpad, int32_t B, co
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_ptr);
     const int total_w = static_cast<int>(h->w_off[h->K]);
-    hipLaunchKernelGGL(rk_backward, dim3(static_cast<unsigned>(B) * h->K), dim3(kThreads), 0, stream, xpad,
+    hipLaunchKernelGGL(rk_backward, dim3(static_cast<unsigned>(rk_grid_groups(B, h->K, 0))), dim3(kThreads), 0, stream, xpad,
                        static_cast<int>(h->row_len), h->lead, h->L, h->C, h->K, h->d_rec, h->d_order, h->d_channels,
-                       h->d_weights, grad_out, F, plane_soft, plane_max, lambda, nl, ns, partial, total_w);
+                       h->d_weights, grad_out, F, plane_soft, plane_max, lambda, nl, ns, partial, total_w, B, 0);
     return hipGetLastError() == hipSuccess ? ROCKET_OK : ROCKET_EHIP;
 }
 

@@ -55,9 +55,10 @@ int rk_launch_forward(const rocket_kernels *h, const float *xpad, int32_t B, uin
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_ptr);
     const int J = static_cast<int>(h->jobs.size());
-    hipLaunchKernelGGL(rk_forward<kThreads>, dim3(static_cast<unsigned>(B) * J), dim3(kThreads), 0, stream, xpad,
+    const int spread = rk_spread(h, B);
+    hipLaunchKernelGGL(rk_forward<kThreads>, dim3(static_cast<unsigned>(rk_grid_groups(B, J, spread))), dim3(kThreads), 0, stream, xpad,
                        static_cast<int>(h->row_len), h->lead, h->L, h->C, J, h->d_rec, h->d_jobs, h->d_channels,
-                       h->d_weights, mask, nl, ns, partials, B);
+                       h->d_weights, mask, nl, ns, partials, B, spread);
     return hipGetLastError() == hipSuccess ? ROCKET_OK : ROCKET_EHIP;
 }
 

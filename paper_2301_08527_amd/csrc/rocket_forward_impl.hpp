@@ -209,8 +209,8 @@ __device__ __forceinline__ void rk_forward_body(const KernelCtx &k, int nout, co
     if ((job.flags & 1) && tail) rk_segment<LEN, 1, NT>(k, rows, 1, tail, st);
 }
 
-// grid: B*J workgroups; workgroup g handles series g / J and job g % J (a row range of
-// one kernel).  It writes the job's partial pooling results: partials holds three planes
+// grid: one workgroup per (series, job), a job being a row range of one kernel; the index
+// mapping is rk_block_to_pair's.  It writes the job's partial pooling results: partials holds three planes
 // of B*J words (max of y - bias, count of y > 0, sum of sigmoids).
 template <int NT>
 #if RK_WPE
@@ -221,11 +221,11 @@ __global__ __launch_bounds__(NT) void rk_forward(const float *__restrict__ xpad,
                                                        const RkJob *__restrict__ jobs,
                                                        const int32_t *__restrict__ channels,
                                                        const float *__restrict__ weights, uint32_t mask, float nl,
-                                                       float ns, float *__restrict__ partials, int B)
+                                                       float ns, float *__restrict__ partials, int B, int spread)
 {
     __shared__ float tile[rk_tile_words(NT)];
-    const int b = blockIdx.x / J;
-    const int jid = blockIdx.x - b * J;
+    int b, jid;
+    if (!rk_block_to_pair(J, B, spread, b, jid)) return;
     const RkJob job = jobs[jid];
     const RkKernelRec rec = recs[job.kernel];
     KernelCtx k = rk_make_ctx(rec, xpad, row_len, lead, L, C, b, channels, weights);
