@@ -90,11 +90,13 @@ def test_lambda_and_shift_sweep(lam, shift):
 
 @pytest.mark.parametrize("B,C,L,K", [(1, 1, 11, 40), (3, 2, 12, 40), (2, 9, 64, 100), (1, 20, 257, 150),
                                      (2, 3, 1025, 120), (1, 12, 4099, 120), (2, 2, 8192, 100), (2, 2, 8193, 100),
-                                     (1, 5, 12289, 160), (1, 3, 20011, 160)])
+                                     (1, 5, 12289, 160), (1, 3, 20011, 160),
+                                     (8, 2, 9001, 60), (11, 3, 9000, 40), (17, 1, 16385, 30)])
 def test_small_and_ragged_shapes(B, C, L, K):
     """shortest legal series, lengths that are not multiples of any tile, one series;
     lengths on both sides of the switch between the one-wavefront kernel (L <= 8192)
-    and the four-wavefront kernel"""
+    and the four-wavefront kernel; batches of 8 and more series that are not multiples of
+    the number of XCDs (the per-XCD series mapping leaves workgroups without a series)"""
     rng = np.random.default_rng(L)
     x = rng.standard_normal((B, C, L)).astype(np.float32)
     h = rocket.rocket_make_kernels(7, K, C, L)
