@@ -143,11 +143,13 @@ int rk_finish_handle(rocket_kernels &h)
             h.kjob_off[k + 1] = static_cast<int32_t>(h.kjob_idx.size());
         }
     }
-    // padded rows: `lead` zeros, the L samples, then zeros: at least the largest padding,
-    // and at least the largest dilation (idle lanes of a partial last row read up to one
-    // row of d floats past the series)
-    h.lead = static_cast<int32_t>(round_up(h.pad_max, 64));
-    h.row_len = round_up(static_cast<int64_t>(h.lead) + h.L + std::max(h.pad_max, max_dil), 64);
+    // padded rows: a gap of `lead` zeros, then the L samples (rounded up to 64 with zeros).  The
+    // gap is at least the largest padding (reads before the series) and at least the largest
+    // dilation (idle lanes of a partial last row read up to one row of d floats past the series);
+    // reads past the end of a row land in the gap of the next row, so one gap serves both sides,
+    // and an all-zero row follows the last one.
+    h.lead = static_cast<int32_t>(round_up(std::max(h.pad_max, max_dil), 64));
+    h.row_len = static_cast<int64_t>(h.lead) + round_up(h.L, 64);
     h.params_dirty = true;
     return ROCKET_OK;
 }
@@ -364,8 +366,9 @@ extern "C" void rocket_free_kernels(rocket_kernels *h)
 // backward kernel][mean and standard deviation of every row, used by the 8-bit entry points]
 static size_t padded_batch_bytes(const rocket_kernels *h, int32_t B)
 {
-    // 8 KB of slack: the LDS staging of the last row may read a few hundred floats past it
-    return static_cast<size_t>(round_up(static_cast<int64_t>(B) * h->C * h->row_len * 4 + 8192, 256));
+    // B*C rows and the all-zero row after them; 8 KB of slack: the LDS staging of the last row may
+    // read a few hundred floats past it
+    return static_cast<size_t>(round_up((static_cast<int64_t>(B) * h->C + 1) * h->row_len * 4 + 8192, 256));
 }
 
 static size_t backward_partial_floats(const rocket_kernels *h) { return static_cast<size_t>(h->w_off[h->K]) + h->K; }

@@ -125,7 +125,7 @@ __device__ __forceinline__ bool rk_block_to_pair(int items, int B, int spread, i
 struct KernelCtx {
     const char *xk;        // padded row of channel 0 of this series, shifted by -p (bytes)
     size_t row_bytes;      // bytes per padded row
-    uint32_t span_bytes;   // bytes from xk to the end of its row
+    uint32_t span_bytes;   // bytes from xk to the end of the zero gap that follows its row
     const int32_t *chans;  // this kernel's channel list
     const float *wts;      // this kernel's weights, channel-major
     int nch, d;
@@ -179,7 +179,7 @@ __device__ __forceinline__ KernelCtx rk_make_ctx(const RkKernelRec &rec, const f
     k.row_bytes = static_cast<size_t>(row_len) * 4;
     k.xk = reinterpret_cast<const char *>(xpad) + static_cast<size_t>(b) * C * k.row_bytes +
            static_cast<size_t>(lead - rec.pad) * 4;
-    k.span_bytes = static_cast<uint32_t>(row_len - (lead - rec.pad)) * 4u;
+    k.span_bytes = static_cast<uint32_t>(row_len + rec.pad) * 4u;   // to the end of the next row's gap
     k.chans = channels + rec.ch_off;
     k.wts = weights + rec.w_off;
     k.nch = rec.nch;

@@ -19,21 +19,23 @@
 //   read leaves its row and "same" padding needs no bounds checks.
 #include "rocket_forward_impl.hpp"
 
-// Copies B*C rows of L floats into rows of row_len floats: `lead` zeros, the
-// samples, zeros to the end.  One thread writes four consecutive floats.
+// Copies nrows rows of L floats into rows of row_len floats: `lead` zeros, the samples, zeros
+// to the end; row number nrows (one past the last) is written as zeros only.  One thread
+// writes four consecutive floats.
 __global__ __launch_bounds__(256) void rk_pad_rows(const float *__restrict__ x, float *__restrict__ xpad,
                                                    int L, int lead, int row_len, int nrows)
 {
     const int col = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (col >= row_len) return;
-    for (int row = blockIdx.y; row < nrows; row += gridDim.y) {
+    for (int row = blockIdx.y; row <= nrows; row += gridDim.y) {
         const float *src = x + static_cast<size_t>(row) * L;
+        const int len = row < nrows ? L : 0;
         float4 v;
         const int s = col - lead;
-        v.x = (s >= 0 && s < L) ? src[s] : 0.f;
-        v.y = (s + 1 >= 0 && s + 1 < L) ? src[s + 1] : 0.f;
-        v.z = (s + 2 >= 0 && s + 2 < L) ? src[s + 2] : 0.f;
-        v.w = (s + 3 >= 0 && s + 3 < L) ? src[s + 3] : 0.f;
+        v.x = (s >= 0 && s < len) ? src[s] : 0.f;
+        v.y = (s + 1 >= 0 && s + 1 < len) ? src[s + 1] : 0.f;
+        v.z = (s + 2 >= 0 && s + 2 < len) ? src[s + 2] : 0.f;
+        v.w = (s + 3 >= 0 && s + 3 < len) ? src[s + 3] : 0.f;
         *reinterpret_cast<float4 *>(xpad + static_cast<size_t>(row) * row_len + col) = v;
     }
 }
@@ -44,7 +46,7 @@ int rk_launch_pad(const rocket_kernels *h, const float *x, int32_t B, float *xpa
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_ptr);
     const int nrows = B * h->C;
-    dim3 grid(static_cast<unsigned>((h->row_len / 4 + 255) / 256), static_cast<unsigned>(nrows < 32768 ? nrows : 32768));
+    dim3 grid(static_cast<unsigned>((h->row_len / 4 + 255) / 256), static_cast<unsigned>(nrows < 32768 ? nrows + 1 : 32768));
     hipLaunchKernelGGL(rk_pad_rows, grid, dim3(256), 0, stream, x, xpad, h->L, h->lead,
                        static_cast<int>(h->row_len), nrows);
     return hipGetLastError() == hipSuccess ? ROCKET_OK : ROCKET_EHIP;

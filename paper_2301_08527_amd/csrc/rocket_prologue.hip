@@ -56,7 +56,8 @@ __global__ __launch_bounds__(256) void rk_row_stats_u8(const uint8_t *__restrict
     }
 }
 
-// Rows of row_len floats: `lead` zeros, the L normalised samples, zeros to the end.
+// Rows of row_len floats: `lead` zeros, the L normalised samples, zeros to the end; row number
+// nrows (one past the last) is written as zeros only.
 __global__ __launch_bounds__(256) void rk_pad_rows_u8(const uint8_t *__restrict__ x,
                                                       const double2 *__restrict__ stats,
                                                       float *__restrict__ xpad, int L, int lead, int row_len,
@@ -64,9 +65,9 @@ __global__ __launch_bounds__(256) void rk_pad_rows_u8(const uint8_t *__restrict_
 {
     const int col = (blockIdx.x * 256 + threadIdx.x) * 4;
     if (col >= row_len) return;
-    for (int row = blockIdx.y; row < nrows; row += gridDim.y) {
+    for (int row = blockIdx.y; row <= nrows; row += gridDim.y) {
         const uint8_t *src = x + static_cast<size_t>(row) * L;
-        const double2 ms = stats[row];
+        const double2 ms = row < nrows ? stats[row] : make_double2(0.0, 0.0);
         const bool live = ms.y > 0.0;
         const double sd = live ? ms.y : 1.0;
         float v[4];
@@ -90,7 +91,7 @@ int rk_launch_pad_u8(const rocket_kernels *h, const uint8_t *x, int32_t B, float
     hipLaunchKernelGGL(rk_row_stats_u8, dim3(static_cast<unsigned>(nrows < 65536 ? nrows : 65536)), dim3(256), 0,
                        stream, x, h->L, nrows, stats);
     if (hipGetLastError() != hipSuccess) return ROCKET_EHIP;
-    dim3 grid(static_cast<unsigned>((h->row_len / 4 + 255) / 256), static_cast<unsigned>(nrows < 32768 ? nrows : 32768));
+    dim3 grid(static_cast<unsigned>((h->row_len / 4 + 255) / 256), static_cast<unsigned>(nrows < 32768 ? nrows + 1 : 32768));
     hipLaunchKernelGGL(rk_pad_rows_u8, grid, dim3(256), 0, stream, x, stats, xpad, h->L, h->lead,
                        static_cast<int>(h->row_len), nrows);
     return hipGetLastError() == hipSuccess ? ROCKET_OK : ROCKET_EHIP;
