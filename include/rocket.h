@@ -4,7 +4,10 @@
  * The library computes the hot path of "Making the 'exceptionally fast' ROCKET
  * model faster": K random dilated, padded, biased 1-D convolution kernels are
  * applied to every (multivariate) series and each kernel output is pooled
- * (paper section 3, parts (1) and (2)).
+ * (paper section 3, parts (1) and (2)), with the backward pass that the soft
+ * pooling allows.  Around it: the input prologue for raw 8-bit samples
+ * (sections 4.1, 4.3), the ridge regressor on the features (part (3), section
+ * 3.3), inference in one call, and a training step on the kernels (section 6).
  *
  * Notation.  Kernel k has length len in {7,9,11}, dilation d >= 1, padding
  * p in {0, (len-1)d/2}, a bias, a list of n_ch distinct channels and one weight

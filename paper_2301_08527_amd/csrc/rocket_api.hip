@@ -1,23 +1,14 @@
-// ROCKET transform for MI355X (gfx950): C-ABI entry points (handles, validation,
-// device mirror, launch sequencing).  The kernels live in rocket_forward.hip and
-// rocket_backward.hip.  See include/rocket.h for the contract of every entry point.
+// ROCKET transform for MI355X (gfx950): C-ABI entry points (handles, validation, host-side
+// plan, device mirror, launch sequencing).  See include/rocket.h for the contract of every
+// entry point.  The kernels live in rocket_forward.hip / rocket_forward_short.hip (transform),
+// rocket_backward.hip (soft-PPV backward), rocket_prologue.hip (8-bit input), rocket_ridge.hip
+// (regressor), rocket_train.hip (loss gradient, parameter update) and rocket_calibrate.hip.
 //
-// Work decomposition of the forward pass (paper section 3, parts (1)-(2)):
-//   one workgroup (256 lanes) owns one (series b, kernel k) pair and produces
-//   its pooled features, so no cross-workgroup combine is needed.
-//   The n outputs of a kernel with dilation d are viewed as a grid of rows of d
-//   consecutive positions: t = m*d + r.  A lane owns a vertical strip of R rows
-//   in one column r, i.e. outputs t0, t0+d, ..., t0+(R-1)d.  Those R outputs
-//   read the R+len-1 inputs x[t0-p+i*d]; each input is loaded once and feeds up
-//   to len fused multiply-adds from registers.  Neighbouring lanes own
-//   neighbouring columns, so every load instruction of a wavefront reads
-//   consecutive floats.  The row range is cut into bands of 16, 8, 4, 2 and 1
-//   rows (binary decomposition of the row count) plus the partial last row, so
-//   every strip is fully valid and the pooling needs no masks.
-//   Weights are wavefront-uniform (scalar registers); max / PPV count / softPPV
-//   sum stay in registers and are closed with wavefront shuffles.
-//   The batch is first copied into a zero-padded workspace so that no dilated
-//   read leaves its row and "same" padding needs no bounds checks.
+// One transform call is: zero-padding copy of the batch into the workspace -> forward kernel
+// (one workgroup per series and job; a job is a time tile of one kernel's outputs and writes
+// partial pooled values) -> rk_finalize (combines a kernel's jobs into the feature planes).
+// One backward call is: the same copy -> backward kernel (one workgroup per series and kernel,
+// per-series partial gradients) -> rk_reduce_batch (sum over the batch in a fixed order).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>

@@ -1,22 +1,25 @@
-// ROCKET transform for MI355X (gfx950): forward kernels (zero-padding copy, conv +
-// pooling) and their launchers.  See include/rocket.h for the contract of the entry points.
+// ROCKET transform for MI355X (gfx950): forward kernels (zero-padding copy, conv + pooling for
+// series longer than 8,192 samples, combination of the partial results) and their launchers.
+// See include/rocket.h for the contract of the entry points.
 //
 // Work decomposition of the forward pass (paper section 3, parts (1)-(2)):
-//   one workgroup (256 lanes) owns one (series b, kernel k) pair and produces
-//   its pooled features, so no cross-workgroup combine is needed.
-//   The n outputs of a kernel with dilation d are viewed as a grid of rows of d
-//   consecutive positions: t = m*d + r.  A lane owns a vertical strip of R rows
-//   in one column r, i.e. outputs t0, t0+d, ..., t0+(R-1)d.  Those R outputs
-//   read the R+len-1 inputs x[t0-p+i*d]; each input is loaded once and feeds up
-//   to len fused multiply-adds from registers.  Neighbouring lanes own
-//   neighbouring columns, so every load instruction of a wavefront reads
-//   consecutive floats.  The row range is cut into bands of 16, 8, 4, 2 and 1
-//   rows (binary decomposition of the row count) plus the partial last row, so
-//   every strip is fully valid and the pooling needs no masks.
-//   Weights are wavefront-uniform (scalar registers); max / PPV count / softPPV
-//   sum stay in registers and are closed with wavefront shuffles.
-//   The batch is first copied into a zero-padded workspace so that no dilated
-//   read leaves its row and "same" padding needs no bounds checks.
+//   The n outputs of a kernel with dilation d are viewed as a grid of rows of d consecutive
+//   positions: t = m*d + r.  A kernel's rows are cut into jobs (time tiles of at least 16,384
+//   positions); one workgroup (256 lanes) owns one (series, job) pair and writes the job's
+//   partial max / positive count / sigmoid sum, which rk_finalize combines per kernel in a fixed
+//   order.  Jobs are sorted by the window of the series they read, so that workgroups running
+//   together share one stretch of one series in L2.
+//   A lane owns a vertical strip of R rows in one column r, i.e. outputs t0, t0+d, ...,
+//   t0+(R-1)d.  Those R outputs read the R+len-1 inputs x[t0-p+i*d]; each input is loaded once
+//   and feeds up to len fused multiply-adds from registers.  Neighbouring lanes own neighbouring
+//   columns, so every load instruction of a wavefront reads consecutive floats.  Three paths,
+//   uniform per workgroup: bands of 32, 16, 8, 4, 2 and 1 rows plus the partial last row, so every
+//   strip is fully valid and the pooling needs no masks (register path); tiles staged through
+//   LDS for dilations below 16; one strip over all rows for large dilations with few rows.
+//   Weights are wavefront-uniform (scalar registers); max / PPV count / softPPV sum stay in
+//   registers and are closed with wavefront shuffles.
+//   The batch is first copied into a zero-padded workspace so that no dilated read leaves the
+//   zeros around its row and "same" padding needs no bounds checks.
 #include "rocket_forward_impl.hpp"
 
 // Copies nrows rows of L floats into rows of row_len floats: `lead` zeros, the samples, zeros
