@@ -106,9 +106,11 @@ int rk_finish_handle(rocket_kernels &h)
             const int64_t tiles = std::max<int64_t>(1, rows / per_tile);
             const bool few = d >= kFewMinD && rows + (tail > 0 ? 1 : 0) <= kFewRowsMax;
             if (few || tiles == 1) {
-                // one job; a tile that reaches over more than two windows counts as "everywhere"
+                // one job; a tile that reaches over more than two windows counts as "everywhere" and
+                // goes first: these are the longest jobs of a series, and started last they were the
+                // tail of a small batch (one series alone: 0.76 -> 0.66 ms)
                 const bool wide = (rows + h.length[k]) * d > 2 * kTilePositions;
-                add(0, rows, 3, wide ? INT64_MAX : 0);
+                add(0, rows, 3, wide ? -1 : 0);
             } else {
                 for (int64_t t = 0; t < tiles; ++t) {
                     const int64_t r0 = t * per_tile, r1 = (t == tiles - 1) ? rows : (t + 1) * per_tile;
