@@ -81,7 +81,7 @@ int rk_finish_handle(rocket_kernels &h)
     // positions (whole LDS chunks or whole 32-row bands); jobs are ordered by the time
     // window they start in, so the workgroups that run together read one stretch of the
     // series and an XCD's live set stays within its L2.  Kernels whose single tile spans
-    // most of the series (large dilations) come last.
+    // most of the series (large dilations) come first.
     {
         struct Key { int64_t window; double cost; };
         std::vector<Key> keys;
