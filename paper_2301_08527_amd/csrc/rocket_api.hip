@@ -7,8 +7,8 @@
 // One transform call is: zero-padding copy of the batch into the workspace -> forward kernel
 // (one workgroup per series and job; a job is a time tile of one kernel's outputs and writes
 // partial pooled values) -> rk_finalize (combines a kernel's jobs into the feature planes).
-// One backward call is: the same copy -> backward kernel (one workgroup per series and kernel,
-// per-series partial gradients) -> rk_reduce_batch (sum over the batch in a fixed order).
+// One backward call is: the same copy -> backward kernel (one workgroup per series and job,
+// per-job partial gradients) -> rk_reduce_jobs (sum over jobs and batch in a fixed order).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -55,7 +55,6 @@ int rk_finish_handle(rocket_kernels &h)
     h.outputs = 0.0;
     h.max_terms = 0;
     int32_t max_dil = 0;
-    std::vector<double> cost(K);
     for (int32_t k = 0; k < K; ++k) {
         h.ch_off[k + 1] = h.ch_off[k] + h.n_ch[k];
         h.w_off[k + 1] = h.w_off[k] + static_cast<int64_t>(h.n_ch[k]) * h.length[k];
@@ -65,19 +64,12 @@ int rk_finish_handle(rocket_kernels &h)
         h.pad_max = std::max(h.pad_max, h.padding[k]);
         max_dil = std::max(max_dil, h.dilation[k]);
         h.max_terms = std::max(h.max_terms, h.n_ch[k] * h.length[k]);
-        cost[k] = static_cast<double>(n) * h.n_ch[k] * h.length[k];
-        h.conv_fma += cost[k];
+        h.conv_fma += static_cast<double>(n) * h.n_ch[k] * h.length[k];
         h.outputs += static_cast<double>(n);
     }
     if (h.w_off[K] > INT32_MAX || h.ch_off[K] > INT32_MAX)
         return rk_fail(ROCKET_EINVAL, "too many weights for 32-bit offsets");
-    // launch order: most expensive kernels first, so the last workgroups to
-    // start are the cheapest and the tail of the launch is short
-    h.order.resize(K);
-    for (int32_t k = 0; k < K; ++k) h.order[k] = k;
-    std::stable_sort(h.order.begin(), h.order.end(),
-                     [&](int32_t a, int32_t b) { return cost[a] > cost[b]; });
-    // Forward jobs.  A kernel's rows are cut into tiles of at least kTilePositions output
+    // Jobs of the forward and the backward pass.  A kernel's rows are cut into tiles of at least kTilePositions output
     // positions (whole LDS chunks or whole 32-row bands); jobs are ordered by the time
     // window they start in, so the workgroups that run together read one stretch of the
     // series and an XCD's live set stays within its L2.  Kernels whose single tile spans
@@ -134,6 +126,16 @@ int rk_finish_handle(rocket_kernels &h)
         for (int32_t k = 0; k < K; ++k) {
             for (int32_t j : per_kernel[k]) h.kjob_idx.push_back(where[j]);
             h.kjob_off[k + 1] = static_cast<int32_t>(h.kjob_idx.size());
+        }
+        // backward pass: words of partial results per job (its kernel's gradient sums, the sum of
+        // q, the largest output and its position, one spare)
+        h.bjob_off.assign(J + 1, 0);
+        int64_t words = 0;
+        for (size_t j = 0; j < J; ++j) {
+            const int32_t k = h.jobs[j].kernel;
+            words += static_cast<int64_t>(h.n_ch[k]) * h.length[k] + 4;
+            if (words > INT32_MAX) return rk_fail(ROCKET_EINVAL, "too many backward partial results per series");
+            h.bjob_off[j + 1] = static_cast<int32_t>(words);
         }
     }
     // padded rows: a gap of `lead` zeros, then the L samples (rounded up to 64 with zeros).  The
@@ -364,7 +366,7 @@ static size_t padded_batch_bytes(const rocket_kernels *h, int32_t B)
     return static_cast<size_t>(round_up((static_cast<int64_t>(B) * h->C + 1) * h->row_len * 4 + 8192, 256));
 }
 
-static size_t backward_partial_floats(const rocket_kernels *h) { return static_cast<size_t>(h->w_off[h->K]) + h->K; }
+static size_t backward_partial_floats(const rocket_kernels *h) { return static_cast<size_t>(h->bjob_off.back()); }
 
 // forward: three words (max, positive count, sigmoid sum) per (series, job)
 static size_t forward_partial_floats(const rocket_kernels *h) { return 3 * h->jobs.size(); }
@@ -390,7 +392,7 @@ static int ensure_device(rocket_kernels *h, hipStream_t stream)
     RK_HIP(hipGetDevice(&cur));
     const int32_t K = h->K;
     const size_t rec_b = round_up(static_cast<int64_t>(K) * sizeof(RkKernelRec), 256);
-    const size_t ord_b = round_up(static_cast<int64_t>(K) * 4, 256);
+    const size_t boff_b = round_up(static_cast<int64_t>(h->bjob_off.size()) * 4, 256);
     const size_t ch_b = round_up(static_cast<int64_t>(h->channels.size()) * 4, 256);
     const size_t w_b = round_up(static_cast<int64_t>(h->weights.size()) * 4, 256);
     const size_t job_b = round_up(static_cast<int64_t>(h->jobs.size()) * sizeof(RkJob), 256);
@@ -399,17 +401,17 @@ static int ensure_device(rocket_kernels *h, hipStream_t stream)
     if (h->d_blob && h->device != cur)
         return rk_fail(ROCKET_EINVAL, "handle was first used on another device");
     if (!h->d_blob) {
-        h->blob_bytes = rec_b + ord_b + ch_b + w_b + job_b + koff_b + kidx_b;
+        h->blob_bytes = rec_b + boff_b + ch_b + w_b + job_b + koff_b + kidx_b;
         RK_HIP(hipMalloc(&h->d_blob, h->blob_bytes));
         h->device = cur;
         char *base = static_cast<char *>(h->d_blob);
         h->d_rec = reinterpret_cast<const RkKernelRec *>(base);
-        h->d_order = reinterpret_cast<const int32_t *>(base + rec_b);
-        h->d_channels = reinterpret_cast<const int32_t *>(base + rec_b + ord_b);
-        h->d_weights = reinterpret_cast<float *>(base + rec_b + ord_b + ch_b);
-        h->d_jobs = reinterpret_cast<const RkJob *>(base + rec_b + ord_b + ch_b + w_b);
-        h->d_kjob_off = reinterpret_cast<const int32_t *>(base + rec_b + ord_b + ch_b + w_b + job_b);
-        h->d_kjob_idx = reinterpret_cast<const int32_t *>(base + rec_b + ord_b + ch_b + w_b + job_b + koff_b);
+        h->d_bjob_off = reinterpret_cast<const int32_t *>(base + rec_b);
+        h->d_channels = reinterpret_cast<const int32_t *>(base + rec_b + boff_b);
+        h->d_weights = reinterpret_cast<float *>(base + rec_b + boff_b + ch_b);
+        h->d_jobs = reinterpret_cast<const RkJob *>(base + rec_b + boff_b + ch_b + w_b);
+        h->d_kjob_off = reinterpret_cast<const int32_t *>(base + rec_b + boff_b + ch_b + w_b + job_b);
+        h->d_kjob_idx = reinterpret_cast<const int32_t *>(base + rec_b + boff_b + ch_b + w_b + job_b + koff_b);
         h->params_dirty = true;
     }
     if (h->params_dirty) {
@@ -424,7 +426,7 @@ static int ensure_device(rocket_kernels *h, hipStream_t stream)
         }
         // pageable sources: these copies return once the source has been read
         RK_HIP(hipMemcpyAsync(const_cast<RkKernelRec *>(h->d_rec), rec.data(), K * sizeof(RkKernelRec), hipMemcpyHostToDevice, stream));
-        RK_HIP(hipMemcpyAsync(const_cast<int32_t *>(h->d_order), h->order.data(), K * 4, hipMemcpyHostToDevice, stream));
+        RK_HIP(hipMemcpyAsync(const_cast<int32_t *>(h->d_bjob_off), h->bjob_off.data(), h->bjob_off.size() * 4, hipMemcpyHostToDevice, stream));
         RK_HIP(hipMemcpyAsync(const_cast<int32_t *>(h->d_channels), h->channels.data(), h->channels.size() * 4, hipMemcpyHostToDevice, stream));
         RK_HIP(hipMemcpyAsync(h->d_weights, h->weights.data(), h->weights.size() * 4, hipMemcpyHostToDevice, stream));
         RK_HIP(hipMemcpyAsync(const_cast<RkJob *>(h->d_jobs), h->jobs.data(), h->jobs.size() * sizeof(RkJob), hipMemcpyHostToDevice, stream));
@@ -555,8 +557,8 @@ static int backward_impl(const char *fn, rocket_kernels *h, const void *x_dev, b
         return rk_fail(ROCKET_EHIP, "launch of the backward kernel failed");
     rc = profile_mark(h, stream, false);
     if (rc != ROCKET_OK) return rc;
-    if (rk_launch_reduce_batch(h, partial, B, grad_w_dev, grad_b_dev, stream) != ROCKET_OK)
-        return rk_fail(ROCKET_EHIP, "launch of the batch reduction kernel failed");
+    if (rk_launch_reduce_jobs(h, partial, xpad, B, grad_out_dev, F, plane_max, grad_w_dev, grad_b_dev, stream) != ROCKET_OK)
+        return rk_fail(ROCKET_EHIP, "launch of the gradient reduction kernel failed");
     return ROCKET_OK;
 }
 

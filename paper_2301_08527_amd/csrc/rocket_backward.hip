@@ -5,7 +5,7 @@
 // ------------------------------------------------------------------ backward kernels
 //
 // Backward pass through softPPV (and, optionally, the max): one workgroup per
-// (series, kernel), the same strip decomposition as the forward pass.  Per strip:
+// (series, job), the same time tiles and strip decomposition as the forward pass.  Per strip:
 //   1. recompute the R conv outputs,
 //   2. turn them into q_i = g_soft * (lambda/n) * s_i (1 - s_i),
 //   3. per channel, re-read the strip's inputs and form the lane's share of
@@ -15,10 +15,11 @@
 //      plain read-modify-write, no atomics, nobody else touches the slot).
 // Lanes without a strip recompute the last strip with a zero coefficient, so control
 // flow stays wavefront-uniform around the cross-lane adds.  At the end the slots are
-// summed and the workgroup writes its partial gradient row partial[b][...]; a second
-// kernel sums the rows over the batch in a fixed order, so results are deterministic.
+// summed and the workgroup writes its job's partial sums; a second kernel sums the jobs
+// of every kernel over the batch in a fixed order, so results are deterministic.
 
 constexpr int kBwdMaxTerms = 9 * 11;     // n_ch <= 9 channels x len <= 11 weights
+constexpr int kReduceThreads = 128;      // >= kBwdMaxTerms + 1: one thread per gradient term of a kernel
 constexpr int kBwdSlots = 16;            // LDS slots per weight: 4 wavefronts x 4 rows of 16 lanes
 
 struct BwdState {
@@ -225,12 +226,12 @@ __device__ __forceinline__ void rk_bwd_band(const KernelCtx &k, int row0, int nc
 // LDS path of the backward pass (d < 8): the chunk's input range is staged once per
 // channel for the conv and once more for the weight gradient.
 template <int LEN, int D>
-__device__ __forceinline__ int rk_bwd_lds_bands(const KernelCtx &k, int rows, float coef, bool want_max, float *tile,
-                                                float *slots, BwdState &st)
+__device__ __forceinline__ int rk_bwd_lds_bands(const KernelCtx &k, int first_row, int end_row, float coef,
+                                                bool want_max, float *tile, float *slots, BwdState &st)
 {
     constexpr int R = kLdsRows;
-    const int nb = rows / R;
-    if (nb == 0) return 0;
+    const int nb = (end_row - first_row) / R;    // whole bands in [first_row, end_row)
+    if (nb == 0) return first_row;
     constexpr int G = kThreads / D;
     const int tid = static_cast<int>(threadIdx.x);
     const int bl_raw = tid / D;
@@ -242,7 +243,7 @@ __device__ __forceinline__ int rk_bwd_lds_bands(const KernelCtx &k, int rows, fl
         const float lane_coef = active ? coef : 0.f;
         const float *mine = tile + bl * R * D + r;
         const int nin = (gb * R + LEN - 1) * D;
-        const uint32_t chunk_bytes = static_cast<uint32_t>(band0 * R * D) * 4u;
+        const uint32_t chunk_bytes = static_cast<uint32_t>((first_row + band0 * R) * D) * 4u;
         float acc[R];
 #pragma unroll
         for (int i = 0; i < R; ++i) acc[i] = 0.f;
@@ -259,7 +260,7 @@ __device__ __forceinline__ int rk_bwd_lds_bands(const KernelCtx &k, int rows, fl
             });
         }
         {
-            const int t0 = ((band0 + bl) * R) * D + r;
+            const int t0 = (first_row + (band0 + bl) * R) * D + r;
             if (want_max) {
 #pragma unroll
                 for (int i = 0; i < R; ++i) {
@@ -291,31 +292,33 @@ __device__ __forceinline__ int rk_bwd_lds_bands(const KernelCtx &k, int rows, fl
             rk_bwd_deposit<LEN>(g, c, slots);
         }
     }
-    return nb * R;
+    return first_row + nb * R;
 }
 
 template <int LEN, int D>
-__device__ __forceinline__ int rk_bwd_lds_dispatch(const KernelCtx &k, int rows, float coef, bool want_max,
-                                                   float *tile, float *slots, BwdState &st)
+__device__ __forceinline__ int rk_bwd_lds_dispatch(const KernelCtx &k, int first_row, int end_row, float coef,
+                                                   bool want_max, float *tile, float *slots, BwdState &st)
 {
     if constexpr (D < kLdsMaxD) {
-        if (k.d == D) return rk_bwd_lds_bands<LEN, D>(k, rows, coef, want_max, tile, slots, st);
-        return rk_bwd_lds_dispatch<LEN, D + 1>(k, rows, coef, want_max, tile, slots, st);
+        if (k.d == D) return rk_bwd_lds_bands<LEN, D>(k, first_row, end_row, coef, want_max, tile, slots, st);
+        return rk_bwd_lds_dispatch<LEN, D + 1>(k, first_row, end_row, coef, want_max, tile, slots, st);
     } else {
-        return 0;
+        return first_row;
     }
 }
 
 template <int LEN>
-__device__ __forceinline__ void rk_backward_body(const KernelCtx &k, int nout, float coef, bool want_max,
-                                                 float *tile, float *slots, BwdState &st)
+__device__ __forceinline__ void rk_backward_body(const KernelCtx &k, int nout, const RkJob job, float coef,
+                                                 bool want_max, float *tile, float *slots, BwdState &st)
 {
     const int d = k.d;
     const int total_rows = nout / d;
     const int tail = nout - total_rows * d;
-    int row0 = 0;
-    if (d < kLdsMaxD) row0 = rk_bwd_lds_dispatch<LEN, 1>(k, total_rows, coef, want_max, tile, slots, st);
-    const int rows = total_rows - row0;   // rows left for the register path
+    // the job's rows: whole LDS chunks first (small dilations), then bands of 32 rows, then the
+    // binary remainder; the job that owns the partial last row does it last
+    int row0 = job.row0;
+    if (d < kLdsMaxD) row0 = rk_bwd_lds_dispatch<LEN, 1>(k, row0, job.row1, coef, want_max, tile, slots, st);
+    const int rows = job.row1 - row0;   // rows left for the register path
     const int nb32 = rows >> 5;
     if (nb32) { rk_bwd_segment<LEN, 32>(k, row0, nb32, d, coef, want_max, slots, st); row0 += nb32 << 5; }
     if (rows & 16) { rk_bwd_band<LEN, 16, 2>(k, row0, d, coef, want_max, slots, st); row0 += 16; }
@@ -323,30 +326,36 @@ __device__ __forceinline__ void rk_backward_body(const KernelCtx &k, int nout, f
     if (rows & 4) { rk_bwd_band<LEN, 4, 8>(k, row0, d, coef, want_max, slots, st); row0 += 4; }
     if (rows & 2) { rk_bwd_band<LEN, 2, 8>(k, row0, d, coef, want_max, slots, st); row0 += 2; }
     if (rows & 1) { rk_bwd_band<LEN, 1, 8>(k, row0, d, coef, want_max, slots, st); row0 += 1; }
-    if (tail) rk_bwd_band<LEN, 1, 8>(k, row0, tail, coef, want_max, slots, st);
+    if ((job.flags & 1) && tail) rk_bwd_band<LEN, 1, 8>(k, total_rows, tail, coef, want_max, slots, st);
 }
 
-// grid: one workgroup per (series, kernel), mapped by rk_block_to_pair.  grad_out is B x (F*K); plane_soft / plane_max are the plane
-// indices of the softPPV and max features in it (plane_max < 0: max not included).
-// partial is B rows of (total_w + K) floats: weight gradients in the layout of
-// `weights`, then the K bias gradients.
+// grid: one workgroup per (series, job), mapped by rk_block_to_pair; a job is a time tile of one
+// kernel's outputs, the same ones the forward pass uses, in the same order (by the window of the
+// series they read), so that workgroups running together share one stretch of one series in L2.
+// grad_out is B x (F*K); plane_soft / plane_max are the plane indices of the softPPV and max
+// features in it (plane_max < 0: max not included).  partial is B rows of `stride` floats; job j
+// owns the words [bjob_off[j], bjob_off[j+1]) of its series' row: the n_ch*len weight-gradient
+// sums of its positions, then the sum of q, the largest z = y - bias, and the first position
+// that attains it.
 __global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict__ xpad, int row_len, int lead, int L, int C, int K,
-                                                        const RkKernelRec *__restrict__ recs,
-                                                        const int32_t *__restrict__ order,
+                                                        int J, const RkKernelRec *__restrict__ recs,
+                                                        const RkJob *__restrict__ jobs,
+                                                        const int32_t *__restrict__ bjob_off,
                                                         const int32_t *__restrict__ channels,
                                                         const float *__restrict__ weights,
                                                         const float *__restrict__ grad_out, int F, int plane_soft,
                                                         int plane_max, float lambda, float nl, float ns,
-                                                        float *__restrict__ partial, int total_w, int B, int spread)
+                                                        float *__restrict__ partial, int stride, int B, int spread)
 {
     __shared__ float tile[kLdsTileWords];
     __shared__ float slots[kBwdMaxTerms * kBwdSlots];
     __shared__ float s_q[kWaves];
     __shared__ float s_max[kWaves];
     __shared__ int s_arg[kWaves];
-    int b, item;
-    if (!rk_block_to_pair(K, B, spread, b, item)) return;
-    const int kid = order[item];
+    int b, jid;
+    if (!rk_block_to_pair(J, B, spread, b, jid)) return;
+    const RkJob job = jobs[jid];
+    const int kid = job.kernel;
     const RkKernelRec rec = recs[kid];
     KernelCtx k = rk_make_ctx(rec, xpad, row_len, lead, L, C, b, channels, weights);
     k.nl = nl;
@@ -365,9 +374,9 @@ __global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict_
     st.qsum = 0.f;
     st.vmax = -INFINITY;
     st.targ = 0;
-    if (rec.len == 7) rk_backward_body<7>(k, rec.nout, coef, want_max, tile, slots, st);
-    else if (rec.len == 9) rk_backward_body<9>(k, rec.nout, coef, want_max, tile, slots, st);
-    else rk_backward_body<11>(k, rec.nout, coef, want_max, tile, slots, st);
+    if (rec.len == 7) rk_backward_body<7>(k, rec.nout, job, coef, want_max, tile, slots, st);
+    else if (rec.len == 9) rk_backward_body<9>(k, rec.nout, job, coef, want_max, tile, slots, st);
+    else rk_backward_body<11>(k, rec.nout, job, coef, want_max, tile, slots, st);
 
     // close the lane reductions: sum of q, and (max, first position) pairs
     float qsum = st.qsum, vmax = st.vmax;
@@ -389,35 +398,75 @@ __global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict_
         gq += s_q[w];
         if (s_max[w] > gm || (s_max[w] == gm && s_arg[w] < ga)) { gm = s_max[w]; ga = s_arg[w]; }
     }
-    const float g_max = want_max ? g_row[static_cast<size_t>(plane_max) * K + kid] : 0.f;
 
-    float *prow = partial + static_cast<size_t>(b) * (static_cast<size_t>(total_w) + K);
+    float *prow = partial + static_cast<size_t>(b) * stride + bjob_off[jid];
     const int t = static_cast<int>(threadIdx.x);
     if (t < nterms) {
         float sum = 0.f;
 #pragma unroll
         for (int l = 0; l < kBwdSlots; ++l) sum += slots[t * kBwdSlots + l];
-        if (want_max) {
-            const int c = t / rec.len, j = t - c * rec.len;
-            const float *xrow = reinterpret_cast<const float *>(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes);
-            sum = fmaf(g_max, xrow[ga + j * rec.dil], sum);
-        }
-        prow[rec.w_off + t] = sum;
+        prow[t] = sum;
     }
-    if (t == 0) prow[total_w + kid] = gq + g_max;
+    if (t == 0) {
+        prow[nterms] = gq;
+        prow[nterms + 1] = gm;
+        reinterpret_cast<int *>(prow)[nterms + 2] = ga;
+    }
 }
 
-// out[i] = sum_b partial[b][i] for i < width, in ascending b; the first total_w
-// entries go to grad_w, the remaining K to grad_b.
-__global__ __launch_bounds__(256) void rk_reduce_batch(const float *__restrict__ partial, int B, int width, int total_w,
-                                                       float *__restrict__ grad_w, float *__restrict__ grad_b)
+// One workgroup per kernel; thread t < n_ch*len owns weight-gradient term t, thread n_ch*len the
+// bias gradient.  Sums the kernel's job partials over the series in ascending b and over the
+// jobs in tile order (a fixed order: results repeat bit for bit), finds per series the first
+// position of the largest output across the jobs, and adds the max plane's sub-gradient there.
+__global__ __launch_bounds__(kReduceThreads) void rk_reduce_jobs(const float *__restrict__ partial, int B, int stride,
+                                                                 const float *__restrict__ xpad, int row_len, int lead, int C,
+                                                                 int K, const RkKernelRec *__restrict__ recs,
+                                                                 const int32_t *__restrict__ kjob_off,
+                                                                 const int32_t *__restrict__ kjob_idx,
+                                                                 const int32_t *__restrict__ bjob_off,
+                                                                 const int32_t *__restrict__ channels,
+                                                                 const float *__restrict__ grad_out, int F, int plane_max,
+                                                                 float *__restrict__ grad_w, float *__restrict__ grad_b)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= width) return;
+    const int kid = blockIdx.x;
+    const RkKernelRec rec = recs[kid];
+    const int nterms = rec.nch * rec.len;
+    const int t = static_cast<int>(threadIdx.x);
+    if (t > nterms) return;
+    const bool want_max = plane_max >= 0;
+    const int q0 = kjob_off[kid], q1 = kjob_off[kid + 1];
+    int chan = 0, tap = 0;
+    if (t < nterms) {
+        const int c = t / rec.len;
+        tap = (t - c * rec.len) * rec.dil;
+        chan = channels[rec.ch_off + c];
+    }
     float sum = 0.f;
-    for (int b = 0; b < B; ++b) sum += partial[static_cast<size_t>(b) * width + i];
-    if (i < total_w) grad_w[i] = sum;
-    else grad_b[i - total_w] = sum;
+    for (int b = 0; b < B; ++b) {
+        const float *prow = partial + static_cast<size_t>(b) * stride;
+        float vmax = -INFINITY;
+        int targ = 0;
+        for (int q = q0; q < q1; ++q) {
+            const float *job = prow + bjob_off[kjob_idx[q]];
+            sum += job[t];                                    // term t, or the sum of q at t == nterms
+            if (want_max) {
+                const float m = job[nterms + 1];
+                const int a = reinterpret_cast<const int *>(job)[nterms + 2];
+                if (m > vmax || (m == vmax && a < targ)) { vmax = m; targ = a; }
+            }
+        }
+        if (want_max) {
+            const float g_max = grad_out[static_cast<size_t>(b) * F * K + static_cast<size_t>(plane_max) * K + kid];
+            if (t < nterms) {
+                const float *xrow = xpad + (static_cast<size_t>(b) * C + chan) * row_len + (lead - rec.pad);
+                sum = fmaf(g_max, xrow[targ + tap], sum);
+            } else {
+                sum += g_max;
+            }
+        }
+    }
+    if (t < nterms) grad_w[rec.w_off + t] = sum;
+    else grad_b[kid] = sum;
 }
 
 // ------------------------------------------------------------------ launchers
@@ -427,20 +476,22 @@ int rk_launch_backward(const rocket_kernels *h, const float *xpad, int32_t B, co
                        void *stream_ptr)
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_ptr);
-    const int total_w = static_cast<int>(h->w_off[h->K]);
-    hipLaunchKernelGGL(rk_backward, dim3(static_cast<unsigned>(rk_grid_groups(B, h->K, 0))), dim3(kThreads), 0, stream, xpad,
-                       static_cast<int>(h->row_len), h->lead, h->L, h->C, h->K, h->d_rec, h->d_order, h->d_channels,
-                       h->d_weights, grad_out, F, plane_soft, plane_max, lambda, nl, ns, partial, total_w, B, 0);
+    const int J = static_cast<int>(h->jobs.size());
+    const int spread = rk_spread(h, B);
+    hipLaunchKernelGGL(rk_backward, dim3(static_cast<unsigned>(rk_grid_groups(B, J, spread))), dim3(kThreads), 0, stream, xpad,
+                       static_cast<int>(h->row_len), h->lead, h->L, h->C, h->K, J, h->d_rec, h->d_jobs, h->d_bjob_off,
+                       h->d_channels, h->d_weights, grad_out, F, plane_soft, plane_max, lambda, nl, ns, partial,
+                       static_cast<int>(h->bjob_off.back()), B, spread);
     return hipGetLastError() == hipSuccess ? ROCKET_OK : ROCKET_EHIP;
 }
 
-int rk_launch_reduce_batch(const rocket_kernels *h, const float *partial, int32_t B, float *grad_w, float *grad_b,
-                           void *stream_ptr)
+int rk_launch_reduce_jobs(const rocket_kernels *h, const float *partial, const float *xpad, int32_t B,
+                          const float *grad_out, int F, int plane_max, float *grad_w, float *grad_b, void *stream_ptr)
 {
     hipStream_t stream = static_cast<hipStream_t>(stream_ptr);
-    const int total_w = static_cast<int>(h->w_off[h->K]);
-    const int width = total_w + h->K;
-    hipLaunchKernelGGL(rk_reduce_batch, dim3((width + 255) / 256), dim3(256), 0, stream, partial, B, width, total_w,
+    hipLaunchKernelGGL(rk_reduce_jobs, dim3(static_cast<unsigned>(h->K)), dim3(kReduceThreads), 0, stream, partial, B,
+                       static_cast<int>(h->bjob_off.back()), xpad, static_cast<int>(h->row_len), h->lead, h->C, h->K,
+                       h->d_rec, h->d_kjob_off, h->d_kjob_idx, h->d_bjob_off, h->d_channels, grad_out, F, plane_max,
                        grad_w, grad_b);
     return hipGetLastError() == hipSuccess ? ROCKET_OK : ROCKET_EHIP;
 }

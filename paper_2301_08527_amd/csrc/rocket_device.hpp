@@ -103,9 +103,10 @@ __device__ __forceinline__ void rk_pool(const float (&acc)[R], uint32_t mask, fl
 // Workgroup index -> (series b, work item).  The hardware deals consecutive workgroups out to
 // the chip's XCDs (kXcds of them, each with its own L2) in turn.  In the plain mapping all XCDs
 // work on the same series at the same time and every L2 fetches the same rows.  With `spread`
-// set (the launcher does so when B >= kXcds) XCD x takes the series with b mod kXcds == x, so each
-// L2 holds rows of its own series only; the grid then has kXcds*ceil(B/kXcds)*items workgroups
-// and the ones whose series does not exist return false.
+// set (the launcher does so when B is a multiple of kXcds) XCD x takes the series with
+// b mod kXcds == x, so each L2 holds rows of its own series only.  (The mapping itself works for
+// any B: the grid then has kXcds*ceil(B/kXcds)*items workgroups and the ones whose series does
+// not exist return false.)
 __device__ __forceinline__ bool rk_block_to_pair(int items, int B, int spread, int &b, int &item)
 {
     const int g = static_cast<int>(blockIdx.x);

@@ -48,12 +48,14 @@ struct rocket_kernels {
     std::vector<float> bias, weights;
     std::vector<int64_t> ch_off, w_off;
 
-    // plan: kernels in launch order (most expensive first), padded row geometry
-    std::vector<int32_t> order;
+    // plan: forward / backward jobs and padded row geometry
     // forward plan: every kernel's rows cut into time tiles; jobs sorted by time window so
     // that workgroups running together read the same stretch of the series
     std::vector<RkJob> jobs;
     std::vector<int32_t> kjob_off, kjob_idx;   // jobs of kernel k: kjob_idx[kjob_off[k] .. kjob_off[k+1])
+    // backward pass: job j owns words [bjob_off[j], bjob_off[j+1]) of a series' row of partial
+    // results (its kernel's n_ch*len gradient sums + 4 words)
+    std::vector<int32_t> bjob_off;
     int32_t pad_max = 0;     // largest padding of any kernel
     int32_t lead = 0;        // zeros in front of every padded row (multiple of 64)
     int64_t row_len = 0;     // floats per padded row (multiple of 64)
@@ -69,10 +71,10 @@ struct rocket_kernels {
     bool host_stale = false;     // the device mirror was updated in place (training) after the last download
     void *update_stream = nullptr;   // stream of that update
     const RkKernelRec *d_rec = nullptr;
-    const int32_t *d_order = nullptr;
     const RkJob *d_jobs = nullptr;
     const int32_t *d_kjob_off = nullptr;
     const int32_t *d_kjob_idx = nullptr;
+    const int32_t *d_bjob_off = nullptr;
     const int32_t *d_channels = nullptr;
     float *d_weights = nullptr;
 
@@ -86,18 +88,19 @@ int rk_fail(int code, const std::string &msg);
 
 // sampler.cpp: fills the per-kernel arrays of `h` (K, C, L already set)
 void rk_sample_kernels(uint64_t seed, rocket_kernels &h);
-// rocket_api.hip: offsets, launch order, padded row geometry; returns ROCKET_OK or an error
+// rocket_api.hip: offsets, job plan, padded row geometry; returns ROCKET_OK or an error
 int rk_finish_handle(rocket_kernels &h);
 
-// Whether a forward launch over B series uses the per-XCD series mapping (rk_block_to_pair in
-// rocket_device.hpp): with at least one series per XCD, and while the kXcds padded series that
-// are then in flight together fit in half of the 256 MB Infinity Cache.  (Measured: 1 % faster
-// and 22 % less L2 fill traffic at 64 x 20 x 50,000; slower at 8 x 20 x 200,000, whose eight
-// padded series are 256 MB; slower for the backward kernel, which therefore never uses it.)
+// Whether a launch over B series uses the per-XCD series mapping (rk_block_to_pair in
+// rocket_device.hpp): when the series divide evenly among the XCDs (with 60 series four XCDs
+// would get 8 and four 7, and the launch takes as long as 64), and while the kXcds padded series
+// that are then in flight together fit in half of the 256 MB Infinity Cache.  (Measured at
+// 64 x 20 x 50,000: 1 % faster, 22 % less L2 fill traffic; slower at 8 x 20 x 200,000, whose eight
+// padded series are 192 MB, and for the short-series kernel, which does not use it.)
 inline int rk_spread(const rocket_kernels *h, int32_t B)
 {
     const int64_t series_bytes = static_cast<int64_t>(h->C) * h->row_len * 4;
-    return (B >= kXcds && kXcds * series_bytes <= (128LL << 20)) ? 1 : 0;
+    return (B % kXcds == 0 && kXcds * series_bytes <= (128LL << 20)) ? 1 : 0;
 }
 // Workgroups of a launch over B series x `items` work items each.
 inline int64_t rk_grid_groups(int32_t B, int64_t items, int spread)
@@ -130,5 +133,7 @@ int rk_launch_finalize(const rocket_kernels *h, const float *partials, int32_t B
                        void *stream);
 int rk_launch_backward(const rocket_kernels *h, const float *xpad, int32_t B, const float *grad_out, int F,
                        int plane_soft, int plane_max, float lambda, float nl, float ns, float *partial, void *stream);
-int rk_launch_reduce_batch(const rocket_kernels *h, const float *partial, int32_t B, float *grad_w, float *grad_b,
-                           void *stream);
+// sums the job partials of every kernel over the jobs and the batch, adds the max plane's
+// sub-gradient at the first arg-max, writes grad_w and grad_b
+int rk_launch_reduce_jobs(const rocket_kernels *h, const float *partial, const float *xpad, int32_t B,
+                          const float *grad_out, int F, int plane_max, float *grad_w, float *grad_b, void *stream);
