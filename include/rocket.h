@@ -113,8 +113,9 @@ int32_t rocket_num_features(uint32_t feature_mask);
  * Returns 0 on invalid arguments.  The workspace holds a zero-padded copy of
  * the batch (so that dilated reads never leave a row) and partial results: for
  * the transform the pooled values of every (series, time tile of a kernel), for
- * the backward pass partial gradients of every (series, time tile of a kernel); and 16 bytes per (series,
- * channel) row for the statistics of the 8-bit entry points.  Its contents are scratch.
+ * the backward pass the partial gradients of every (series, time tile of a
+ * kernel); and 16 bytes per (series, channel) row for the statistics of the
+ * 8-bit entry points.  Its contents are scratch.
  */
 size_t rocket_workspace_bytes(const rocket_kernels *kernels, int32_t B, uint32_t feature_mask, int backward);
 
