@@ -179,6 +179,19 @@ int rocket_soft_ppv_backward_u8(rocket_kernels *kernels, const uint8_t *x_u8_dev
                                 float *grad_w_dev, float *grad_b_dev,
                                 void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * The work decomposition, for inspection and tests.  The outputs of kernel k are viewed as
+ * rows of d consecutive positions (position t = row*d + column); its n / d full rows are cut
+ * into jobs (time tiles), one workgroup per (series, job) in both passes.  Job j covers rows
+ * [row0[j], row1[j]) of kernel kernel[j]; bit 0 of flags[j] says that it also owns the partial
+ * last row (the n mod d positions after the full rows), bit 1 that it is the only job of its
+ * kernel.  Jobs are listed in launch order.  The pointers are borrowed from the handle
+ * (host memory, *count entries each, stride_bytes apart: they point into an array of records).
+ */
+int rocket_jobs_view_get(const rocket_kernels *kernels, int32_t *count, const int32_t **kernel,
+                         const int32_t **row0, const int32_t **row1, const int32_t **flags,
+                         int32_t *stride_bytes);
+
 /* Algorithmic work of one call, for roofline accounting: *conv_fma receives
  * sum_k n_k*n_ch_k*len_k (fused multiply-adds per series of the forward conv),
  * *outputs receives sum_k n_k (pooled positions per series). */

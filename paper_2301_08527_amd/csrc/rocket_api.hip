@@ -288,6 +288,22 @@ extern "C" int rocket_kernels_set_params(rocket_kernels *h, const float *weights
     return ROCKET_OK;
 }
 
+extern "C" int rocket_jobs_view_get(const rocket_kernels *h, int32_t *count, const int32_t **kernel,
+                                    const int32_t **row0, const int32_t **row1, const int32_t **flags,
+                                    int32_t *stride_bytes)
+{
+    if (!h || !count || !kernel || !row0 || !row1 || !flags || !stride_bytes)
+        return rk_fail(ROCKET_EINVAL, "rocket_jobs_view_get: NULL argument");
+    static_assert(std::is_standard_layout<RkJob>::value, "RkJob is exposed field by field");
+    *count = static_cast<int32_t>(h->jobs.size());
+    *kernel = &h->jobs.data()->kernel;
+    *row0 = &h->jobs.data()->row0;
+    *row1 = &h->jobs.data()->row1;
+    *flags = &h->jobs.data()->flags;
+    *stride_bytes = static_cast<int32_t>(sizeof(RkJob));
+    return ROCKET_OK;
+}
+
 extern "C" int rocket_work_per_series(const rocket_kernels *h, double *conv_fma, double *outputs)
 {
     if (!h) return rk_fail(ROCKET_EINVAL, "rocket_work_per_series: NULL handle");

@@ -21,7 +21,7 @@ EXPORTS = [
     "rocket_make_kernels", "rocket_kernels_import", "rocket_kernels_view_get",
     "rocket_kernels_set_params", "rocket_num_features", "rocket_workspace_bytes",
     "rocket_transform", "rocket_soft_ppv_backward", "rocket_transform_u8", "rocket_soft_ppv_backward_u8",
-    "rocket_work_per_series",
+    "rocket_work_per_series", "rocket_jobs_view_get",
     "rocket_profile_enable", "rocket_profile_read", "rocket_calibrate_fma",
     "rocket_ridge_workspace_bytes", "rocket_ridge_fit", "rocket_ridge_predict", "rocket_infer",
     "rocket_mse_grad", "rocket_sgd_update", "rocket_train_workspace_bytes", "rocket_train_step",
@@ -73,6 +73,7 @@ def load_library():
     lib.rocket_soft_ppv_backward.argtypes = [vp, vp, i32, u32, vp, f32, f32, C.c_int, vp, vp, vp, C.c_size_t, vp]
     lib.rocket_transform_u8.argtypes = lib.rocket_transform.argtypes
     lib.rocket_soft_ppv_backward_u8.argtypes = lib.rocket_soft_ppv_backward.argtypes
+    lib.rocket_jobs_view_get.argtypes = [vp, C.POINTER(i32)] + [C.POINTER(C.POINTER(i32))] * 4 + [C.POINTER(i32)]
     lib.rocket_work_per_series.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.rocket_profile_enable.argtypes = [vp, C.c_int]
     lib.rocket_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]
@@ -180,6 +181,18 @@ def rocket_kernels_set_params(kernels, weights=None, bias=None):
 
 def rocket_workspace_bytes(kernels, B, feature_mask, backward=False):
     return int(load_library().rocket_workspace_bytes(kernels.handle, B, feature_mask, int(bool(backward))))
+
+
+def rocket_jobs_view_get(kernels):
+    """dict of int32 arrays (copies): kernel, row0, row1, flags of every job, in launch order."""
+    n, stride = C.c_int32(), C.c_int32()
+    ptrs = [C.POINTER(C.c_int32)() for _ in range(4)]
+    _check(load_library().rocket_jobs_view_get(kernels.handle, C.byref(n), *[C.byref(p) for p in ptrs], C.byref(stride)))
+    step = stride.value // 4
+    out = {}
+    for name, p in zip(("kernel", "row0", "row1", "flags"), ptrs):
+        out[name] = np.ctypeslib.as_array(p, shape=(n.value * step,))[::step].copy()
+    return out
 
 
 def rocket_work_per_series(kernels):

@@ -132,3 +132,34 @@ def test_subset_keeps_the_chosen_kernels():
         assert np.array_equal(ks["channels"][ks["ch_off"][i]:ks["ch_off"][i + 1]], kr["channels"][kr["ch_off"][k]:kr["ch_off"][k + 1]])
     with pytest.raises(rocket.RocketError):
         rocket.rocket_kernels_subset(h, np.array([50], np.int32))
+
+
+@pytest.mark.parametrize("K,C,L", [(300, 3, 700), (400, 20, 50000), (200, 1, 8193), (300, 5, 200001)])
+def test_job_plan_partitions_every_kernel(K, C, L):
+    """host-only: the jobs of a kernel cover its full rows exactly once, in order, exactly one
+    of them owns the partial last row, and tile boundaries are whole bands"""
+    h = rocket.rocket_make_kernels(11, K, C, L)
+    kr = rocket.rocket_kernels_view_get(h)
+    jobs = rocket.rocket_jobs_view_get(h)
+    n = L + 2 * kr["padding"].astype(np.int64) - (kr["length"].astype(np.int64) - 1) * kr["dilation"]
+    rows = n // kr["dilation"]
+    assert set(jobs["kernel"].tolist()) == set(range(K))
+    total_positions = 0
+    for k in range(K):
+        mine = np.nonzero(jobs["kernel"] == k)[0]
+        r0, r1, fl = jobs["row0"][mine], jobs["row1"][mine], jobs["flags"][mine]
+        order = np.argsort(r0, kind="stable")
+        r0, r1, fl = r0[order], r1[order], fl[order]
+        assert r0[0] == 0 and r1[-1] == rows[k]
+        assert np.all(r0[1:] == r1[:-1])                       # contiguous, no overlap
+        assert np.all(r1[:-1] > r0[:-1]) and r1[-1] >= r0[-1]  # only a last tile may hold no full row
+        assert (fl & 1).sum() == 1 and fl[-1] & 1              # the last tile owns the partial last row
+        assert np.all(((fl & 2) != 0) == (len(mine) == 1))
+        d = int(kr["dilation"][k])
+        if len(mine) > 1:
+            unit = 17 * (256 // d) if d < 16 else 32          # whole LDS chunks / whole 32-row bands
+            assert np.all(r1[:-1] % unit == 0)
+            assert np.all((r1[:-1] - r0[:-1]) * d >= 16384)    # tiles of at least 16,384 positions
+        total_positions += int(n[k])
+    fma, outs = rocket.rocket_work_per_series(h)
+    assert outs == total_positions
