@@ -113,6 +113,28 @@ def test_argument_validation_without_gpu():
     # backward needs the softPPV plane
     assert lib.rocket_soft_ppv_backward(h.handle, dummy, 1, 3, dummy, 10.0, -3.0, 0, dummy, dummy, dummy, 1 << 30, None) == rocket.ROCKET_EINVAL
     assert lib.rocket_soft_ppv_backward(h.handle, dummy, 1, 4, dummy, 10.0, -3.0, 1, dummy, dummy, dummy, 1 << 30, None) == rocket.ROCKET_EINVAL
+    # the 8-bit, inference and training entry points validate the same way, before any GPU call
+    E = rocket.ROCKET_EINVAL
+    assert lib.rocket_transform_u8(h.handle, dummy, 0, 3, 10.0, -3.0, dummy, dummy, 1 << 30, None) == E
+    assert lib.rocket_transform_u8(h.handle, None, 1, 3, 10.0, -3.0, dummy, dummy, 1 << 30, None) == E
+    assert lib.rocket_soft_ppv_backward_u8(h.handle, dummy, 1, 3, dummy, 10.0, -3.0, 0, dummy, dummy, dummy, 1 << 30, None) == E
+    assert lib.rocket_infer(h.handle, dummy, 0, 1, 3, 10.0, -3.0, None, dummy, dummy, dummy, dummy, 1 << 30, None) == E
+    assert lib.rocket_infer(h.handle, dummy, 1, 0, 3, 10.0, -3.0, dummy, dummy, dummy, dummy, dummy, 1 << 30, None) == E
+    assert lib.rocket_mse_grad(None, dummy, dummy, 4, 10, dummy, dummy, None) == E
+    assert lib.rocket_mse_grad(dummy, dummy, dummy, 0, 10, dummy, dummy, None) == E
+    assert lib.rocket_mse_grad(dummy, dummy, dummy, 70000, 10, dummy, dummy, None) == E
+    assert lib.rocket_sgd_update(h.handle, None, dummy, 0.1, 0, None) == E
+    assert lib.rocket_sgd_update(h.handle, dummy, dummy, float("inf"), 0, None) == E
+    assert lib.rocket_train_workspace_bytes(h.handle, 0, 5) == 0
+    need = lib.rocket_train_workspace_bytes(h.handle, 4, 5)
+    assert need > rocket.rocket_workspace_bytes(h, 4, 5, backward=True) and need % 256 == 0
+    args = (h.handle, dummy, 0, 4, 3, 10.0, -3.0, dummy, dummy, dummy, 0.1, 0, dummy, dummy, 1 << 40, None)
+    assert lib.rocket_train_step(*args) == E                       # mask without softPPV
+    args = (h.handle, dummy, 0, 4, 5, 10.0, -3.0, dummy, dummy, dummy, 0.1, 0, dummy, dummy, 16, None)
+    assert lib.rocket_train_step(*args) == rocket.ROCKET_EWORKSPACE
+    assert lib.rocket_kernels_subset(h.handle, None, 1, ctypes.byref(ctypes.c_void_p())) == E
+    assert lib.rocket_jobs_view_get(h.handle, None, None, None, None, None, None) == E
+    assert lib.rocket_calibrate_fma(None, None) == E
     h.free()
     rocket.load_library().rocket_free_kernels(None)
 
