@@ -20,7 +20,15 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X datasheet, packed FP32 on the vector ALUs
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "rk_forward_hbm_traffic.json")
+# HBM-side bytes per launch of the dominant kernel, from the two `rocprofv3 --pmc` runs (FETCH_SIZE,
+# WRITE_SIZE, each scaled by what the counter reads for the padding copy of known size) whose summaries
+# are under profiles/: (workload, batch, feature mask) -> bytes.  Other shapes report null.
+MEASURED_TRAFFIC = {
+    # profiles/rk_forward_multivariate-20x50k.md: 9,828,772 KiB x 1.968 fetched + 58,058 KiB x 1.001 written
+    ("multivariate-20x50k", 64, 3): 19866767900,
+    # profiles/rk_backward_multivariate-20x50k-grad.md: 48,181,176 KiB x 1.968 + 168,806 KiB x 1.001
+    ("multivariate-20x50k-grad", 60, 5): 97269276630,
+}
 
 WORKLOADS = {
     # name: (synth config, feature mask or None = the config's, description)
@@ -209,14 +217,7 @@ def main():
     pool_flops = outputs_per_series * B * (10.0 if with_grad else pool_per_pos)
     achieved_with_pooling = (flops_per_launch + pool_flops) / (kernel_ms_avg * 1e-3) / 1e12
     plain_fma_ceiling = None if args.lean else rocket.rocket_calibrate_fma()
-    traffic = None
-    if os.path.exists(TRAFFIC_FILE):
-        try:
-            rec = json.load(open(TRAFFIC_FILE))
-            if rec.get("workload") == args.workload and rec.get("batch") == B and rec.get("features") == mask:
-                traffic = rec.get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+    traffic = MEASURED_TRAFFIC.get((args.workload, B, mask))
 
     line = {
         "metric": ("examples/sec (20ch x 50k, K=10k) and % of FP32 vector peak" if cfg_id == 2 else
