@@ -39,6 +39,7 @@ WORKLOADS = {
     "univariate-standard": 1,
     "univariate-tiny": 0,
     "long-20x200k": 4,
+    "ridge-677x20000": None,          # the regressor at the paper's sizes: one step = one fit + one 64-row predict
 }
 
 
@@ -99,6 +100,36 @@ def quick_rate(rocket, synth, torch, cfg_id, lam, steps=20, warmup=3):
             "value": B / dt, "unit": "series/s", "ms_per_step": 1e3 * dt, "conv_tflops": 2.0 * fma * B / dt / 1e12}
 
 
+def ridge_bench(args, torch, rocket):
+    """The ridge regressor at the paper's sizes (677 training examples x 20,000 features):
+    a step is one fit followed by one prediction of 64 rows."""
+    n, p, m = 677, 20000, 64
+    rng = np.random.Generator(np.random.PCG64(677))
+    X = torch.from_numpy(rng.standard_normal((n, p)).astype(np.float32)).cuda()
+    y = torch.from_numpy((0.6 + 1.2 * rng.random(n)).astype(np.float32)).cuda()
+    ws = torch.empty(rocket.rocket_ridge_workspace_bytes(n, p), dtype=torch.uint8, device="cuda")
+
+    def step():
+        coef, b = rocket.rocket_ridge_fit(X, y, 1.0, workspace=ws)
+        return rocket.rocket_ridge_predict(X[:m], coef, b)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    print(json.dumps({
+        "metric": "ridge fits/sec (677 x 20,000, fp64, dual form) with a 64-row predict each",
+        "value": 1.0 / dt, "unit": "fits/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * dt, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": args.workload, "n": n, "p": p, "predict_rows": m, "alpha": 1.0},
+    }))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -114,6 +145,9 @@ def main():
         print("bench.py: no GPU visible; the transform has no CPU path", file=sys.stderr)
         sys.exit(1)
 
+    if args.workload == "ridge-677x20000":
+        ridge_bench(args, torch, rocket)
+        return
     cfg_id = WORKLOADS[args.workload]
     cfg = synth.CONFIGS[cfg_id]
     B = cfg["B"] if args.batch is None else args.batch
