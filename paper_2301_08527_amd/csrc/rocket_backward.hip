@@ -86,7 +86,8 @@ __device__ __forceinline__ void rk_bwd_segment(const KernelCtx &k, int row0, int
         float acc[R];
 #pragma unroll
         for (int i = 0; i < R; ++i) acc[i] = 0.f;
-        for (int c = 0; c < k.nch; ++c) {
+        const int last = k.nch - 1;
+        for (int c = 0; c < last; ++c) {
             const __amdgpu_buffer_rsrc_t row =
                 rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
             float w[LEN];
@@ -97,6 +98,25 @@ __device__ __forceinline__ void rk_bwd_segment(const KernelCtx &k, int row0, int
                 constexpr int i = decltype(ic)::value;
                 rk_taps<LEN, R, i>(w, rk_load(row, voff, soff), acc);
                 soff = rk_advance(soff, dbytes);
+            });
+        }
+        // the last channel's inputs stay in registers: its weight gradient below needs no second read
+        float xlast[R + LEN - 1];
+        {
+            const __amdgpu_buffer_rsrc_t row =
+                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[last]) * k.row_bytes, k.span_bytes);
+            float w[LEN];
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) w[j] = k.wts[last * LEN + j];
+            uint32_t soff = 0;
+            rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                xlast[i] = rk_load(row, voff, soff);
+                soff = rk_advance(soff, dbytes);
+            });
+            rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                rk_taps<LEN, R, i>(w, xlast[i], acc);
             });
         }
         if (want_max) {
@@ -110,7 +130,21 @@ __device__ __forceinline__ void rk_bwd_segment(const KernelCtx &k, int row0, int
             acc[i] = rk_q(acc[i], lane_coef, k.nl, k.ns);   // acc now holds q
             st.qsum += acc[i];
         }
-        for (int c = 0; c < k.nch; ++c) {
+        {
+            float g[LEN];
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) g[j] = 0.f;
+            rk_static_for<0, R + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                rk_static_for<0, LEN>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+                    constexpr int o = i - j;
+                    if constexpr (o >= 0 && o < R) g[j] = fmaf(acc[o], xlast[i], g[j]);
+                });
+            });
+            rk_bwd_deposit<LEN>(g, last, slots);
+        }
+        for (int c = 0; c < last; ++c) {
             const __amdgpu_buffer_rsrc_t row =
                 rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
             float g[LEN];
@@ -273,10 +307,15 @@ __device__ __forceinline__ int rk_bwd_lds_bands(const KernelCtx &k, int first_ro
                 st.qsum += acc[i];
             }
         }
-        for (int c = 0; c < k.nch; ++c) {
-            const __amdgpu_buffer_rsrc_t row =
-                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
-            rk_stage_tile<kThreads>(row, chunk_bytes, nin, tile);
+        // the tile still holds the last channel of the conv: its weight gradient goes first and
+        // needs no second staging; the other channels are staged again
+        for (int cc = 0; cc < k.nch; ++cc) {
+            const int c = cc == 0 ? k.nch - 1 : cc - 1;
+            if (cc > 0) {
+                const __amdgpu_buffer_rsrc_t row =
+                    rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+                rk_stage_tile<kThreads>(row, chunk_bytes, nin, tile);
+            }
             float g[LEN];
 #pragma unroll
             for (int j = 0; j < LEN; ++j) g[j] = 0.f;
