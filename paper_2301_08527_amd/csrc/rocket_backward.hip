@@ -20,6 +20,7 @@
 
 constexpr int kBwdMaxTerms = 9 * 11;     // n_ch <= 9 channels x len <= 11 weights
 constexpr int kReduceThreads = 128;      // >= kBwdMaxTerms + 1: one thread per gradient term of a kernel
+constexpr int kBwdFewRowsMax = 20;       // most rows of a kernel that takes the few-rows path (register budget)
 constexpr int kBwdSlots = 16;            // LDS slots per weight: 4 wavefronts x 4 rows of 16 lanes
 
 struct BwdState {
@@ -257,6 +258,106 @@ __device__ __forceinline__ void rk_bwd_band(const KernelCtx &k, int row0, int nc
     }
 }
 
+// Kernels with a large dilation have few rows (n / d): all of them, the partial last row
+// included, form one strip per lane, so every input value is loaded once per pass instead of
+// once per band of a 8/4/2/1 cascade.  As in the forward pass the row count is a run-time
+// uniform: window rows past it, and window rows that lie wholly in the zero padding, are
+// skipped (loads and multiply-adds) with scalar branches.  The conv's last channel is the
+// weight gradient's first, with its inputs still in registers.
+template <int LEN, int RM>
+__device__ __forceinline__ void rk_bwd_few_rows(const KernelCtx &k, int rows, int tail, float coef, bool want_max,
+                                                float *slots, BwdState &st)
+{
+    const int nrows = rows + (tail > 0 ? 1 : 0);            // rows with at least one output
+    const int prow = k.pad / k.d;                           // padding in rows: 0 or (LEN-1)/2
+    const int data_rows = (k.L + k.d - 1) / k.d;            // input rows that hold samples
+    const uint32_t dbytes = static_cast<uint32_t>(k.d) * 4u;
+    // bit i: window row i is needed (i < nrows+LEN-1) and holds samples (0 <= i-prow < data_rows)
+    uint32_t live = 0;
+    for (int i = 0; i < nrows + LEN - 1; ++i) {
+        if (i >= prow && i - prow < data_rows) live |= 1u << i;
+    }
+    // single scalar bit tests on an opaque copy, instead of twenty-odd precomputed lane masks
+    auto is_live = [&](int i) {
+        uint32_t word = live;
+        asm volatile("" : "+s"(word));
+        return ((word >> i) & 1u) != 0;
+    };
+    const int tid = static_cast<int>(threadIdx.x);
+    const int wave0 = __builtin_amdgcn_readfirstlane(tid & ~63);
+    const int last = k.nch - 1;
+    for (int base = 0; base < k.d; base += kThreads) {      // uniform trip count
+        if (base + wave0 >= k.d) continue;                  // no column for this wavefront in this pass
+        const int r_raw = base + tid;
+        const bool lane_ok = r_raw < k.d;
+        const int r = lane_ok ? r_raw : k.d - 1;            // idle lanes shadow the last column with weight 0
+        const uint32_t voff = static_cast<uint32_t>(r) * 4u;
+        float acc[RM];
+#pragma unroll
+        for (int i = 0; i < RM; ++i) acc[i] = 0.f;
+        float xv[RM + LEN - 1];
+        for (int c = 0; c <= last; ++c) {                   // xv keeps the inputs of channel `last`
+            const __amdgpu_buffer_rsrc_t row =
+                rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+            float w[LEN];
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
+            uint32_t soff = 0;
+            rk_static_for<0, RM + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                if (is_live(i)) xv[i] = rk_load(row, voff, soff);
+                soff = rk_advance(soff, dbytes);
+            });
+            rk_static_for<0, RM + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                if (is_live(i)) rk_taps<LEN, RM, i>(w, xv[i], acc);
+            });
+        }
+        // rows below `rows` are complete; row `rows` exists only in the first `tail` columns
+        const int own_rows = lane_ok ? (rows + (r < tail ? 1 : 0)) : 0;
+        rk_static_for<0, RM>([&](auto oc) {
+            constexpr int o = decltype(oc)::value;
+            int lim = nrows;
+            asm volatile("" : "+s"(lim));
+            float q = 0.f;
+            if (o < lim) {                                  // uniform
+                const bool own = o < own_rows;
+                if (want_max && own && acc[o] > st.vmax) { st.vmax = acc[o]; st.targ = o * k.d + r; }
+                q = rk_q(acc[o], own ? coef : 0.f, k.nl, k.ns);
+                st.qsum += q;
+            }
+            acc[o] = q;                                     // acc now holds q (0 for rows that do not exist)
+        });
+        for (int cc = 0; cc <= last; ++cc) {
+            const int c = cc == 0 ? last : cc - 1;
+            float g[LEN];
+#pragma unroll
+            for (int j = 0; j < LEN; ++j) g[j] = 0.f;
+            if (cc > 0) {
+                const __amdgpu_buffer_rsrc_t row =
+                    rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
+                uint32_t soff = 0;
+                rk_static_for<0, RM + LEN - 1>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    if (is_live(i)) xv[i] = rk_load(row, voff, soff);
+                    soff = rk_advance(soff, dbytes);
+                });
+            }
+            rk_static_for<0, RM + LEN - 1>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                if (is_live(i)) {
+                    rk_static_for<0, LEN>([&](auto jc) {
+                        constexpr int j = decltype(jc)::value;
+                        constexpr int o = i - j;
+                        if constexpr (o >= 0 && o < RM) g[j] = fmaf(acc[o], xv[i], g[j]);
+                    });
+                }
+            });
+            rk_bwd_deposit<LEN>(g, c, slots);
+        }
+    }
+}
+
 // LDS path of the backward pass (d < 8): the chunk's input range is staged once per
 // channel for the conv and once more for the weight gradient.
 template <int LEN, int D>
@@ -355,6 +456,11 @@ __device__ __forceinline__ void rk_backward_body(const KernelCtx &k, int nout, c
     const int tail = nout - total_rows * d;
     // the job's rows: whole LDS chunks first (small dilations), then bands of 32 rows, then the
     // binary remainder; the job that owns the partial last row does it last
+    if ((job.flags & 2) && d >= kFewMinD) {       // uniform: the kernel's only job, large dilation
+        const int nrows = total_rows + (tail > 0 ? 1 : 0);
+        if (nrows <= 8) { rk_bwd_few_rows<LEN, 8>(k, total_rows, tail, coef, want_max, slots, st); return; }
+        if (nrows <= kBwdFewRowsMax) { rk_bwd_few_rows<LEN, kBwdFewRowsMax>(k, total_rows, tail, coef, want_max, slots, st); return; }
+    }
     int row0 = job.row0;
     if (d < kLdsMaxD) row0 = rk_bwd_lds_dispatch<LEN, 1>(k, row0, job.row1, coef, want_max, tile, slots, st);
     const int rows = job.row1 - row0;   // rows left for the register path
