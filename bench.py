@@ -26,8 +26,8 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X datasheet, packed FP32 on the vector 
 MEASURED_TRAFFIC = {
     # profiles/rk_forward_multivariate-20x50k.md: 9,828,772 KiB x 1.968 fetched + 58,058 KiB x 1.001 written
     ("multivariate-20x50k", 64, 3): 19866767900,
-    # profiles/rk_backward_multivariate-20x50k-grad.md: 47,013,697 KiB x 1.968 + 168,806 KiB x 1.001
-    ("multivariate-20x50k-grad", 60, 5): 94916536076,
+    # profiles/rk_backward_multivariate-20x50k-grad.md: 20,025,199 KiB x 1.968 + 168,805 KiB x 1.001
+    ("multivariate-20x50k-grad", 60, 5): 40528449964,
 }
 
 WORKLOADS = {
