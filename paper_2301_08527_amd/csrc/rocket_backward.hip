@@ -74,12 +74,14 @@ __device__ __forceinline__ void rk_bwd_segment(const KernelCtx &k, int row0, int
     const int step_band = kThreads / ncols, step_r = kThreads - step_band * ncols;   // uniform
     int band_run = (nbands == 1) ? 0 : static_cast<int>(threadIdx.x) / ncols;
     int r_run = static_cast<int>(threadIdx.x) - band_run * ncols;
+    const int wave0 = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) & ~63);   // first lane of this wavefront
     for (int base = 0; base < nstrips; base += kThreads, band_run += step_band, r_run += step_r) {   // uniform trip count
         if (r_run >= ncols) { r_run -= ncols; ++band_run; }
+        if (base + wave0 >= nstrips) continue;      // no strip left for this wavefront in this pass
         const int s_raw = base + static_cast<int>(threadIdx.x);
         const bool valid = s_raw < nstrips;
         const float lane_coef = valid ? coef : 0.f;
-        // idle lanes redo the segment's last strip with weight 0
+        // idle lanes of a wavefront that still has strips redo the segment's last strip with weight 0
         const int band = valid ? band_run : nbands - 1;
         const int r = valid ? r_run : ncols - 1;
         const int t0 = (row0 + band * R) * k.d + r;
