@@ -94,7 +94,21 @@ int rk_finish_handle(rocket_kernels &h)
                 keys.push_back({window, pos * per_pos});
             };
             const int64_t unit = d < kLdsMaxD ? kLdsRows * (kThreads / d) : 32;     // rows per LDS chunk / tallest band
-            const int64_t per_tile = unit * std::max<int64_t>(1, (kTilePositions + unit * d - 1) / (unit * d));
+            int64_t units = std::max<int64_t>(1, (kTilePositions + unit * d - 1) / (unit * d));
+            if (d >= kLdsMaxD) {
+                // register path: a tile of `units` bands has units*d strips, handed out 64 to a
+                // wavefront; between the smallest tile and twice that, take the height that leaves
+                // the fewest lanes of the last wavefront without a strip
+                int64_t best = units;
+                double best_idle = 2.0;
+                for (int64_t u = units; u <= units + (units + 1) / 2; ++u) {
+                    const int64_t strips = u * d, slots = (strips + 63) / 64 * 64;
+                    const double idle = static_cast<double>(slots - strips) / static_cast<double>(slots);
+                    if (idle < best_idle - 1e-9) { best_idle = idle; best = u; }
+                }
+                units = best;
+            }
+            const int64_t per_tile = unit * units;
             const int64_t tiles = std::max<int64_t>(1, rows / per_tile);
             const bool few = d >= kFewMinD && rows + (tail > 0 ? 1 : 0) <= kFewRowsMax;
             if (few || tiles == 1) {
