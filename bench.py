@@ -24,8 +24,8 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X datasheet, packed FP32 on the vector 
 # WRITE_SIZE, each scaled by what the counter reads for the padding copy of known size) whose summaries
 # are under profiles/: (workload, batch, feature mask) -> bytes.  Other shapes report null.
 MEASURED_TRAFFIC = {
-    # profiles/rk_forward_multivariate-20x50k.md: 9,828,772 KiB x 1.968 fetched + 58,058 KiB x 1.001 written
-    ("multivariate-20x50k", 64, 3): 19866767900,
+    # profiles/rk_forward_multivariate-20x50k.md: 12,581,194 KiB x 1.968 fetched + 59,074 KiB x 1.001 written
+    ("multivariate-20x50k", 64, 3): 25414576462,
     # profiles/rk_backward_multivariate-20x50k-grad.md: 20,025,199 KiB x 1.968 + 168,805 KiB x 1.001
     ("multivariate-20x50k-grad", 60, 5): 40528449964,
 }
