@@ -118,7 +118,9 @@ __device__ __forceinline__ void rk_few_rows(const KernelCtx &k, int rows, int ta
         asm volatile("" : "+s"(word));
         return ((word >> (i & 31)) & 1u) != 0;
     };
+    const int wave0 = __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) & ~63);   // first lane of this wavefront
     for (int base = 0; base < k.d; base += NT) {      // uniform trip count
+        if (base + wave0 >= k.d) continue;            // no column left for this wavefront in this pass
         const int r_raw = base + static_cast<int>(threadIdx.x);
         const bool lane_ok = r_raw < k.d;
         const int r = lane_ok ? r_raw : k.d - 1;            // idle lanes shadow the last column
