@@ -131,3 +131,19 @@ def test_backward_is_repeatable_and_overwrites():
     # every sum is taken in a fixed order without atomics: the bits repeat
     assert np.array_equal(gw.cpu().numpy(), a)
     assert np.array_equal(gb.cpu().numpy(), b)
+
+
+def test_batch_that_uses_the_per_xcd_mapping():
+    """8 series of more than 8,192 samples: the launch maps series to XCDs; all planes, max included"""
+    rng = np.random.default_rng(77)
+    B, C, L, K = 8, 2, 9001, 48
+    x = rng.standard_normal((B, C, L)).astype(np.float32)
+    h = rocket.rocket_make_kernels(3, K, C, L)
+    kr = rocket.rocket_kernels_view_get(h)
+    grad_out = rng.standard_normal((B, 3 * K)).astype(np.float32)
+    print("backward, per-XCD mapping", flush=True)
+    gw, gb = _backward(h, x, 7, grad_out, 10.0, -3.0, True)
+    g_soft, g_max = _split(grad_out, 7, K)
+    sel = np.nonzero(_stable_argmax(x, kr))[0].astype(np.int32)
+    assert len(sel) > K // 2
+    check_backward(x, kr, gw, gb, g_soft, g_max, 10.0, -3.0, sel=sel)
