@@ -29,6 +29,11 @@ library) are:
   dilation    floor(2^(u * log2((L-1)/(len-1)))), clamped to
               [1, floor((L-1)/(len-1))]
   padding     low bit of a u32:  (len-1)*dilation/2 zeros on each side, or 0
+  logarithm   the accept test of the normal draws and the two floors above must
+  and power   fall the same way wherever the sampler runs, so ln, log2 and 2^y
+              are not taken from a math library: they are the short series
+              below (ln_series, exp2_series), built from IEEE additions,
+              multiplications and divisions only, every one in a stated order
 """
 import math
 
@@ -41,6 +46,44 @@ MUL2 = 0x94D049BB133111EB
 ROU_C = 0.8577638849607068  # sqrt(2/e), half-width of the ratio-of-uniforms box
 TWO_M53 = 2.0 ** -53
 TWO_M23 = 2.0 ** -23
+LN2 = 0.6931471805599453        # ln 2, nearest double
+SQRT_HALF = 0.7071067811865476  # sqrt(1/2), nearest double
+LN_TERMS = 12                   # odd powers z, z^3, ... z^25 of the atanh series
+EXP_TERMS = 19                  # Taylor terms of exp on [0, ln 2)
+
+
+def ln_series(x):
+    """Natural logarithm of a positive finite double.  x = m * 2^e with m in
+    [sqrt(1/2), sqrt(2)); ln m = 2 atanh(z), z = (m-1)/(m+1), |z| < 0.172, by
+    its series sum_i z^(2i+1)/(2i+1), i = 0..LN_TERMS, summed from the smallest
+    term (Horner in z^2).  Truncation error below 1e-19; every operation is an
+    IEEE double operation in the order written."""
+    m, e = math.frexp(x)            # exact: m in [0.5, 1)
+    if m < SQRT_HALF:
+        m = m * 2.0                 # exact
+        e -= 1
+    z = (m - 1.0) / (m + 1.0)
+    z2 = z * z
+    s = 1.0 / (2 * LN_TERMS + 1)
+    for i in range(LN_TERMS - 1, -1, -1):
+        s = s * z2 + 1.0 / (2 * i + 1)
+    return e * LN2 + (2.0 * z) * s
+
+
+def log2_series(x):
+    return ln_series(x) / LN2
+
+
+def exp2_series(y):
+    """2^y for 0 <= y < 1000: 2^floor(y) * exp(t), t = (y - floor(y)) * ln 2 in
+    [0, ln 2), exp by its Taylor polynomial of degree EXP_TERMS in nested form
+    (truncation error below 1e-19), scaled by the exact power of two."""
+    n = math.floor(y)
+    t = (y - n) * LN2
+    s = 1.0
+    for i in range(EXP_TERMS, 0, -1):
+        s = 1.0 + (s * t) / i
+    return math.ldexp(s, int(n))
 
 
 def mix64(z):
@@ -77,7 +120,7 @@ class Stream:
             u = self.u_open()
             v = ROU_C * (2.0 * self.u01() - 1.0)
             x = v / u
-            if x * x <= -4.0 * math.log(u):
+            if x * x <= -4.0 * ln_series(u):
                 return x
 
 
@@ -87,7 +130,7 @@ def sample_kernel(seed, k, C, L):
     length = 7 + 2 * ((st.u32() * 3) >> 32)
 
     m = min(C, 9)
-    n_ch = int(math.floor(2.0 ** (st.u01() * math.log2(m + 1))))
+    n_ch = int(math.floor(exp2_series(st.u01() * log2_series(float(m + 1)))))
     n_ch = max(1, min(n_ch, m))
 
     idx = list(range(C))
@@ -109,7 +152,7 @@ def sample_kernel(seed, k, C, L):
     bias = np.float32((st.u32() >> 8) * TWO_M23 - 1.0)
 
     ratio = (L - 1) / (length - 1)
-    dilation = int(math.floor(2.0 ** (st.u01() * math.log2(ratio))))
+    dilation = int(math.floor(exp2_series(st.u01() * log2_series(ratio))))
     dilation = max(1, min(dilation, (L - 1) // (length - 1)))
 
     padding = ((length - 1) * dilation) // 2 if (st.u32() & 1) else 0

@@ -5,6 +5,13 @@
 // SplitMix64 stream keyed by (seed, kernel index); each draw uses one 64-bit
 // output.  Order of draws: length, channel count, channel subset, weights
 // (channel by channel), bias, dilation, padding.
+//
+// The accept test of the normal draws and the floors that give the channel count and
+// the dilation depend on a logarithm and on a power of two.  A math library's last-bit
+// rounding differs between machines and could turn such a decision, so the three
+// functions are spelt out here (natural_log, two_to_the) as short series of IEEE
+// additions, multiplications and divisions in a fixed order; anyone who repeats the
+// same operations gets the same kernels.
 #include <cmath>
 #include <numeric>
 
@@ -19,6 +26,38 @@ inline uint64_t scramble(uint64_t z)
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
     return z ^ (z >> 31);
+}
+
+constexpr double kLn2 = 0.6931471805599453;        // ln 2, nearest double
+constexpr double kSqrtHalf = 0.7071067811865476;   // sqrt(1/2), nearest double
+constexpr int kLogTerms = 12;                      // atanh series: z^(2i+1)/(2i+1), i = 0..12
+constexpr int kExpTerms = 19;                      // Taylor polynomial of exp on [0, ln 2)
+
+// ln x for positive finite x: x = m*2^e with m in [sqrt(1/2), sqrt(2)), ln m = 2 atanh((m-1)/(m+1))
+// by its odd series, summed from the smallest term.  Truncation error below 1e-19.
+double natural_log(double x)
+{
+    int e = 0;
+    double m = std::frexp(x, &e);   // exact
+    if (m < kSqrtHalf) { m = m * 2.0; e -= 1; }
+    const double z = (m - 1.0) / (m + 1.0);
+    const double z2 = z * z;
+    double s = 1.0 / static_cast<double>(2 * kLogTerms + 1);
+    for (int i = kLogTerms - 1; i >= 0; --i) s = s * z2 + 1.0 / static_cast<double>(2 * i + 1);
+    return static_cast<double>(e) * kLn2 + (2.0 * z) * s;
+}
+
+double log_base2(double x) { return natural_log(x) / kLn2; }
+
+// 2^y for 0 <= y < 1000: the integer part is an exact scaling, the fraction goes through
+// exp(t), t in [0, ln 2), as a nested Taylor polynomial.  Truncation error below 1e-19.
+double two_to_the(double y)
+{
+    const double n = std::floor(y);
+    const double t = (y - n) * kLn2;
+    double s = 1.0;
+    for (int i = kExpTerms; i >= 1; --i) s = 1.0 + (s * t) / static_cast<double>(i);
+    return std::ldexp(s, static_cast<int>(n));
 }
 
 class KernelStream {
@@ -41,7 +80,7 @@ public:
             const double u = unit_open();
             const double v = 0.8577638849607068 * (2.0 * unit() - 1.0);
             const double ratio = v / u;
-            if (ratio * ratio <= -4.0 * std::log(u)) return ratio;
+            if (ratio * ratio <= -4.0 * natural_log(u)) return ratio;
         }
     }
 
@@ -58,7 +97,7 @@ void rk_sample_kernels(uint64_t seed, rocket_kernels &h)
     h.n_ch.resize(K); h.bias.resize(K);
     h.channels.clear(); h.weights.clear();
     const int32_t max_ch = C < 9 ? C : 9;
-    const double ch_span = std::log2(static_cast<double>(max_ch + 1));
+    const double ch_span = log_base2(static_cast<double>(max_ch + 1));
     std::vector<int32_t> pool(C);
     std::vector<double> row(11);
 
@@ -66,7 +105,7 @@ void rk_sample_kernels(uint64_t seed, rocket_kernels &h)
         KernelStream rng(seed, static_cast<uint64_t>(k));
         const int32_t len = 7 + 2 * static_cast<int32_t>(rng.below(3));
 
-        int32_t nch = static_cast<int32_t>(std::floor(std::exp2(rng.unit() * ch_span)));
+        int32_t nch = static_cast<int32_t>(std::floor(two_to_the(rng.unit() * ch_span)));
         if (nch < 1) nch = 1;
         if (nch > max_ch) nch = max_ch;
 
@@ -86,8 +125,8 @@ void rk_sample_kernels(uint64_t seed, rocket_kernels &h)
 
         h.bias[k] = static_cast<float>(static_cast<double>(rng.word() >> 8) * 0x1.0p-23 - 1.0);
 
-        const double span = std::log2(static_cast<double>(L - 1) / static_cast<double>(len - 1));
-        int32_t dil = static_cast<int32_t>(std::floor(std::exp2(rng.unit() * span)));
+        const double span = log_base2(static_cast<double>(L - 1) / static_cast<double>(len - 1));
+        int32_t dil = static_cast<int32_t>(std::floor(two_to_the(rng.unit() * span)));
         const int32_t dil_max = (L - 1) / (len - 1);
         if (dil < 1) dil = 1;
         if (dil > dil_max) dil = dil_max;

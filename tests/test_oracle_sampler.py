@@ -37,6 +37,30 @@ def test_uniform_conversions():
     assert abs(sampler.ROU_C - math.sqrt(2.0 / math.e)) < 1e-16
 
 
+def test_series_logarithm_and_power_against_the_math_library():
+    """the sampler's own ln / log2 / 2^y (series of basic operations, so that its decisions do
+    not depend on a math library's last bit) agree with the library functions to a few ulp, hit
+    the exact values, and are monotone across the range-reduction seams"""
+    rng = np.random.default_rng(8)
+    xs = np.concatenate([rng.random(20000), 10.0 ** rng.uniform(-12, 8, 20000), [1.0, 0.5, 2.0, 2.0 ** -53, 8333.0]])
+    for x in xs:
+        x = float(x)
+        if x <= 0.0:
+            continue
+        want = math.log(x)
+        assert abs(sampler.ln_series(x) - want) <= 4e-16 * max(1.0, abs(want))
+        assert abs(sampler.log2_series(x) - math.log2(x)) <= 6e-16 * max(1.0, abs(math.log2(x)))
+    for y in np.concatenate([rng.uniform(0, 16, 20000), [0.0, 1.0, 3.0, 13.0, 15.999999999]]):
+        y = float(y)
+        assert abs(sampler.exp2_series(y) - 2.0 ** y) <= 4e-16 * 2.0 ** y
+    assert sampler.ln_series(1.0) == 0.0 and sampler.exp2_series(0.0) == 1.0 and sampler.exp2_series(5.0) == 32.0
+    assert abs(sampler.LN2 - math.log(2.0)) < 1e-16 and abs(sampler.SQRT_HALF - math.sqrt(0.5)) < 1e-16
+    seam = [sampler.ln_series(sampler.SQRT_HALF * (1.0 + i * 1e-16)) for i in range(-40, 41)]
+    assert all(b >= a - 2e-16 for a, b in zip(seam, seam[1:]))
+    ints = [sampler.exp2_series(4.0 + i * 2.0 ** -50) for i in range(-8, 9)]
+    assert all(b >= a for a, b in zip(ints, ints[1:]))
+
+
 def test_normal_draws_are_standard_normal():
     """a wrong box width or acceptance test skews the law: KS against N(0,1)"""
     st = sampler.Stream(5, 1)
