@@ -139,7 +139,8 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2301_08527_amd import rocket, synth
+    import synth
+    from paper_2301_08527_amd import rocket
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the transform has no CPU path", file=sys.stderr)

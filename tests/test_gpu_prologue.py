@@ -5,7 +5,8 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_2301_08527_amd import rocket, synth
+import synth
+from paper_2301_08527_amd import rocket
 from parity import check_backward, check_forward
 
 pytestmark = pytest.mark.gpu

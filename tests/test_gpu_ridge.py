@@ -5,7 +5,8 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_2301_08527_amd import rocket, synth
+import synth
+from paper_2301_08527_amd import rocket
 
 pytestmark = pytest.mark.gpu
 

@@ -5,7 +5,7 @@ import numpy as np
 from scipy.stats import zscore
 
 import oracle
-from paper_2301_08527_amd import synth
+import synth
 
 
 def test_matches_scipy_zscore():
