@@ -40,6 +40,14 @@ __device__ __forceinline__ float rk_q(float z, float coef, float nl, float ns)
     return coef * sg * (e * sg);
 }
 
+// Running (largest z, first position that attains it) of a lane.  A lane does not always meet
+// its positions in increasing order (with d > 256 its next column block, 256 positions on, comes
+// after its next row, d positions on), so an exact tie keeps the smaller position.
+__device__ __forceinline__ void rk_track_max(float z, int t, BwdState &st)
+{
+    if (z > st.vmax || (z == st.vmax && t < st.targ)) { st.vmax = z; st.targ = t; }
+}
+
 // Sum over each row of 16 lanes (all 16 lanes end up with the row sum).
 __device__ __forceinline__ float rk_row16_sum(float v)
 {
@@ -125,7 +133,7 @@ __device__ __forceinline__ void rk_bwd_segment(const KernelCtx &k, int row0, int
         if (want_max) {
 #pragma unroll
             for (int i = 0; i < R; ++i) {
-                if (acc[i] > st.vmax) { st.vmax = acc[i]; st.targ = t0 + i * k.d; }
+                rk_track_max(acc[i], t0 + i * k.d, st);
             }
         }
 #pragma unroll
@@ -223,7 +231,7 @@ __device__ __forceinline__ void rk_bwd_band(const KernelCtx &k, int row0, int nc
                 if (want_max) {
 #pragma unroll
                     for (int i = 0; i < R; ++i) {
-                        if (acc[s][i] > st.vmax) { st.vmax = acc[s][i]; st.targ = t0[s] + i * k.d; }
+                        rk_track_max(acc[s][i], t0[s] + i * k.d, st);
                     }
                 }
 #pragma unroll
@@ -324,7 +332,7 @@ __device__ __forceinline__ void rk_bwd_few_rows(const KernelCtx &k, int rows, in
             float q = 0.f;
             if (o < lim) {                                  // uniform
                 const bool own = o < own_rows;
-                if (want_max && own && acc[o] > st.vmax) { st.vmax = acc[o]; st.targ = o * k.d + r; }
+                if (want_max && own) rk_track_max(acc[o], o * k.d + r, st);
                 q = rk_q(acc[o], own ? coef : 0.f, k.nl, k.ns);
                 st.qsum += q;
             }
@@ -360,7 +368,7 @@ __device__ __forceinline__ void rk_bwd_few_rows(const KernelCtx &k, int rows, in
     }
 }
 
-// LDS path of the backward pass (d < 8): the chunk's input range is staged once per
+// LDS path of the backward pass (d < kLdsMaxD): the chunk's input range is staged once per
 // channel for the conv and once more for the weight gradient.
 template <int LEN, int D>
 __device__ __forceinline__ int rk_bwd_lds_bands(const KernelCtx &k, int first_row, int end_row, float coef,
@@ -401,7 +409,7 @@ __device__ __forceinline__ int rk_bwd_lds_bands(const KernelCtx &k, int first_ro
             if (want_max) {
 #pragma unroll
                 for (int i = 0; i < R; ++i) {
-                    if (acc[i] > st.vmax) { st.vmax = acc[i]; st.targ = t0 + i * D; }
+                    rk_track_max(acc[i], t0 + i * D, st);
                 }
             }
 #pragma unroll
