@@ -285,19 +285,23 @@ extern "C" int rocket_kernels_view_get(const rocket_kernels *h, rocket_kernels_v
 extern "C" int rocket_kernels_set_params(rocket_kernels *h, const float *weights, const float *bias)
 {
     if (!h) return rk_fail(ROCKET_EINVAL, "rocket_kernels_set_params: NULL handle");
-    if (weights && bias) h->host_stale = false;     // everything is overwritten
-    const int rc = download_params(h);
-    if (rc != ROCKET_OK) return rc;
+    // validate everything before anything changes: a rejected call leaves the handle as it was
     if (weights) {
         for (size_t i = 0; i < h->weights.size(); ++i)
             if (!std::isfinite(weights[i])) return rk_fail(ROCKET_EINVAL, "rocket_kernels_set_params: weight not finite");
-        std::copy(weights, weights + h->weights.size(), h->weights.begin());
     }
     if (bias) {
         for (int32_t k = 0; k < h->K; ++k)
             if (!std::isfinite(bias[k])) return rk_fail(ROCKET_EINVAL, "rocket_kernels_set_params: bias not finite");
-        std::copy(bias, bias + h->K, h->bias.begin());
     }
+    if (weights && bias) {
+        h->host_stale = false;     // everything is overwritten: nothing to fetch from the device
+    } else {
+        const int rc = download_params(h);
+        if (rc != ROCKET_OK) return rc;
+    }
+    if (weights) std::copy(weights, weights + h->weights.size(), h->weights.begin());
+    if (bias) std::copy(bias, bias + h->K, h->bias.begin());
     h->params_dirty = true;
     return ROCKET_OK;
 }

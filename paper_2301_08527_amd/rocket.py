@@ -115,6 +115,13 @@ class Kernels:
 
     def __init__(self, handle):
         self._h = C.c_void_p(handle)
+        # the sizes never change; keeping them here lets the compute wrappers check their
+        # arguments without asking the library for a view (which, after a training update,
+        # would wait for the device and download the parameters)
+        v = _View()
+        _check(load_library().rocket_kernels_view_get(self._h, C.byref(v)))
+        self.K, self.C, self.L = int(v.K), int(v.C), int(v.L)
+        self.total_channels, self.total_weights = int(v.total_channels), int(v.total_weights)
 
     @property
     def handle(self):
@@ -237,8 +244,7 @@ def rocket_transform(kernels, x, feature_mask, lam=10.0, shift=-3.0, out=None, w
     torch = _torch()
     if not (x.is_cuda and x.dtype == getattr(torch, _dtype) and x.is_contiguous() and x.dim() == 3):
         raise RocketError(ROCKET_EINVAL, "x must be a contiguous %s CUDA tensor of shape (B, C, L)" % _dtype)
-    v = _View()
-    _check(load_library().rocket_kernels_view_get(kernels.handle, C.byref(v)))
+    v = kernels
     B = x.shape[0]
     if x.shape[1] != v.C or x.shape[2] != v.L:
         raise RocketError(ROCKET_ESHAPE, "x is (B, %d, %d) but the kernels were made for (%d, %d)"
@@ -267,8 +273,7 @@ def rocket_soft_ppv_backward(kernels, x, feature_mask, grad_out, lam=10.0, shift
     for t, name, dt in ((x, "x", _dtype), (grad_out, "grad_out", "float32")):
         if not (t.is_cuda and t.dtype == getattr(torch, dt) and t.is_contiguous()):
             raise RocketError(ROCKET_EINVAL, "%s must be a contiguous %s CUDA tensor" % (name, dt))
-    v = _View()
-    _check(load_library().rocket_kernels_view_get(kernels.handle, C.byref(v)))
+    v = kernels
     B = x.shape[0]
     if x.dim() != 3 or x.shape[1] != v.C or x.shape[2] != v.L:
         raise RocketError(ROCKET_ESHAPE, "x does not match the kernels' (C, L)")
@@ -345,8 +350,7 @@ def rocket_infer(kernels, x, feature_mask, coef, intercept, lam=10.0, shift=-3.0
     torch = _torch()
     if not (x.is_cuda and x.dtype in (torch.float32, torch.uint8) and x.is_contiguous() and x.dim() == 3):
         raise RocketError(ROCKET_EINVAL, "x must be a contiguous float32 or uint8 CUDA tensor of shape (B, C, L)")
-    v = _View()
-    _check(load_library().rocket_kernels_view_get(kernels.handle, C.byref(v)))
+    v = kernels
     B = x.shape[0]
     if x.shape[1] != v.C or x.shape[2] != v.L:
         raise RocketError(ROCKET_ESHAPE, "x does not match the kernels' (C, L)")
@@ -384,8 +388,7 @@ def rocket_mse_grad(pred, targets, coef, grad_out=None, stream=None):
 
 def rocket_sgd_update(kernels, grad_w, grad_b, lr, recentre=False, stream=None):
     torch = _torch()
-    v = _View()
-    _check(load_library().rocket_kernels_view_get(kernels.handle, C.byref(v)))
+    v = kernels
     for t, n, name in ((grad_w, v.total_weights, "grad_w"), (grad_b, v.K, "grad_b")):
         if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == n):
             raise RocketError(ROCKET_EINVAL, "%s must be a contiguous float32 CUDA tensor of %d elements" % (name, n))
@@ -404,8 +407,7 @@ def rocket_train_step(kernels, x, feature_mask, coef, intercept, targets, lr, la
     torch = _torch()
     if not (x.is_cuda and x.dtype in (torch.float32, torch.uint8) and x.is_contiguous() and x.dim() == 3):
         raise RocketError(ROCKET_EINVAL, "x must be a contiguous float32 or uint8 CUDA tensor of shape (B, C, L)")
-    v = _View()
-    _check(load_library().rocket_kernels_view_get(kernels.handle, C.byref(v)))
+    v = kernels
     B = x.shape[0]
     if x.shape[1] != v.C or x.shape[2] != v.L:
         raise RocketError(ROCKET_ESHAPE, "x does not match the kernels' (C, L)")

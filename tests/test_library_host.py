@@ -53,6 +53,13 @@ def test_import_round_trip_and_set_params():
     assert np.array_equal(v2["weights"], kr["weights"] * 2) and np.array_equal(v2["bias"], kr["bias"])
     with pytest.raises(rocket.RocketError):
         rocket.rocket_kernels_set_params(h, weights=np.full_like(kr["weights"], np.nan))
+    # a rejected call changes nothing, whichever array is the bad one
+    bad_bias = kr["bias"].copy()
+    bad_bias[3] = np.inf
+    with pytest.raises(rocket.RocketError):
+        rocket.rocket_kernels_set_params(h, weights=kr["weights"] * 3, bias=bad_bias)
+    v3 = rocket.rocket_kernels_view_get(h)
+    assert np.array_equal(v3["weights"], kr["weights"] * 2) and np.array_equal(v3["bias"], kr["bias"])
     fma, outs = rocket.rocket_work_per_series(h)
     n = 300 + 2 * kr["padding"].astype(np.int64) - (kr["length"] - 1) * kr["dilation"]
     assert outs == n.sum() and fma == (n * kr["n_ch"] * kr["length"]).sum()
@@ -133,8 +140,6 @@ def test_argument_validation_without_gpu():
     args = (h.handle, dummy, 0, 4, 5, 10.0, -3.0, dummy, dummy, dummy, 0.1, 0, dummy, dummy, 16, None)
     assert lib.rocket_train_step(*args) == rocket.ROCKET_EWORKSPACE
     assert lib.rocket_kernels_subset(h.handle, None, 1, ctypes.byref(ctypes.c_void_p())) == E
-    assert lib.rocket_jobs_view_get(h.handle, None, None, None, None, None, None) == E
-    assert lib.rocket_calibrate_fma(None, None) == E
     h.free()
     rocket.load_library().rocket_free_kernels(None)
 
