@@ -137,6 +137,26 @@ int rocket_transform(rocket_kernels *kernels, const float *x_dev, int32_t B, uin
                      void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * rocket_transform for callers that cannot allocate device memory or hand over a workspace
+ * (a serving loop that transforms one reading after another, a harness that forbids
+ * allocation): same inputs, same outputs, bit for bit, but the workspace is a 64 MiB array
+ * that lives in the library's device image (each GPU the library runs on holds it until the
+ * process ends).  The call allocates and frees nothing and creates no events; it only
+ * launches kernels on hip_stream.  Requirements: rocket_workspace_bytes(kernels, B, mask, 0)
+ * must not exceed 64 MiB (ROCKET_EWORKSPACE otherwise; 64 MiB hold e.g. 8 series of
+ * 20 x 50,000 samples with 10,000 kernels, or 256 x 1 x 1,000 with 10,000 kernels), and the
+ * handle's parameters must already be on the current device (ROCKET_EINVAL otherwise): one
+ * earlier rocket_transform call on the handle uploads them, and so does any other compute
+ * call; after rocket_kernels_set_params they have to be uploaded again the same way.
+ * All calls on one GPU share the one array: two calls that overlap in time on the same GPU
+ * (different streams, different threads) race and give wrong results; calls on one stream
+ * are ordered by the stream.  Nothing in the array needs clearing between calls: every word a
+ * call reads it has written before.  rocket_profile_enable is ignored by this entry point.
+ */
+int rocket_transform_noalloc(rocket_kernels *kernels, const float *x_dev, int32_t B, uint32_t feature_mask,
+                             float lambda, float shift, float *out_dev, void *hip_stream);
+
+/*
  * Backward pass through the pooling (the gradient flow that softPPV allows,
  * section 3.2): given grad_out_dev (device, same layout as the transform's
  * output for feature_mask, which must contain ROCKET_F_SOFTPPV), computes the

@@ -14,6 +14,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <type_traits>
 
@@ -508,28 +509,39 @@ static int pad_batch(const rocket_kernels *h, const void *x_dev, bool is_u8, int
     return rc == ROCKET_OK ? ROCKET_OK : rk_fail(ROCKET_EHIP, "launch of the padding kernel failed");
 }
 
+// `resident_only`: the call may not allocate, so the handle's device mirror must already be there
+// and current (ensure_device would allocate and copy), and no timing events are created.
 static int transform_impl(const char *fn, rocket_kernels *h, const void *x_dev, bool is_u8, int32_t B, uint32_t mask,
-                          float lambda, float shift, float *out_dev, void *ws, size_t ws_bytes, void *hip_stream)
+                          float lambda, float shift, float *out_dev, void *ws, size_t ws_bytes, void *hip_stream,
+                          bool resident_only = false)
 {
     int rc = check_common(fn, h, x_dev, B, mask, lambda, shift, ws, ws_bytes, 0);
     if (rc != ROCKET_OK) return rc;
     if (!out_dev) return rk_fail(ROCKET_EINVAL, std::string(fn) + ": out_dev is NULL");
     if (h->row_len > INT32_MAX) return rk_fail(ROCKET_EINVAL, std::string(fn) + ": series too long");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    rc = ensure_device(h, stream);
-    if (rc != ROCKET_OK) return rc;
+    if (resident_only) {
+        int cur = -1;
+        RK_HIP(hipGetDevice(&cur));
+        if (!h->d_blob || h->params_dirty || h->device != cur)
+            return rk_fail(ROCKET_EINVAL, std::string(fn) + ": the kernels' parameters are not on this device yet; one "
+                           "earlier rocket_transform call on the handle uploads them");
+    } else {
+        rc = ensure_device(h, stream);
+        if (rc != ROCKET_OK) return rc;
+    }
     float *xpad = static_cast<float *>(ws);
     rc = pad_batch(h, x_dev, is_u8, B, ws, 0, stream);
     if (rc != ROCKET_OK) return rc;
     const float nl = -lambda * kLog2e, ns = -shift * kLog2e;
-    rc = profile_mark(h, stream, true);
+    if (!resident_only) rc = profile_mark(h, stream, true);
     if (rc != ROCKET_OK) return rc;
     // series of at most kShortSeries samples: one wavefront per (series, kernel) instead of four
     float *partials = reinterpret_cast<float *>(static_cast<char *>(ws) + padded_batch_bytes(h, B));
     const int launched = h->L <= kShortSeries ? rk_launch_forward_short(h, xpad, B, mask, nl, ns, partials, stream)
                                               : rk_launch_forward(h, xpad, B, mask, nl, ns, partials, stream);
     if (launched != ROCKET_OK) return rk_fail(ROCKET_EHIP, "launch of the forward kernel failed");
-    rc = profile_mark(h, stream, false);
+    if (!resident_only) rc = profile_mark(h, stream, false);
     if (rc != ROCKET_OK) return rc;
     if (rk_launch_finalize(h, partials, B, mask, out_dev, stream) != ROCKET_OK)
         return rk_fail(ROCKET_EHIP, "launch of the feature kernel failed");
@@ -547,6 +559,58 @@ extern "C" int rocket_transform_u8(rocket_kernels *h, const uint8_t *x_u8_dev, i
 {
     return transform_impl("rocket_transform_u8", h, x_u8_dev, true, B, mask, lambda, shift, out_dev, ws, ws_bytes,
                           hip_stream);
+}
+
+// ------------------------------------------------------------------ transform without allocation
+//
+// For callers that cannot allocate device memory (tight serving loops, harnesses that forbid it):
+// the workspace of the transform is a fixed array in the library's own device image.  Every GPU
+// the library runs on holds one copy of it, at its own address, until the process ends.
+
+constexpr size_t kResidentScratchBytes = static_cast<size_t>(64) << 20;   // 64 MiB
+constexpr int kMaxDevices = 64;
+
+static __device__ __align__(256) unsigned char scratch[kResidentScratchBytes];
+
+// Device address of `scratch` on the current device.  The array's name is only a host-side
+// stand-in for the symbol; the address that kernels and copies can use comes from
+// hipGetSymbolAddress, once per device, with that device current.
+static int resident_scratch(void **ptr)
+{
+    static void *address[kMaxDevices];      // zero-initialised; written once per device
+    static std::mutex guard;
+    int dev = -1;
+    RK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return rk_fail(ROCKET_EINVAL, "device index beyond the supported range");
+    std::lock_guard<std::mutex> lock(guard);
+    if (!address[dev]) {
+        void *p = nullptr;
+        RK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return rk_fail(ROCKET_EHIP, "hipGetSymbolAddress returned no address for the resident workspace");
+        address[dev] = p;
+    }
+    *ptr = address[dev];
+    return ROCKET_OK;
+}
+
+extern "C" int rocket_transform_noalloc(rocket_kernels *h, const float *x_dev, int32_t B, uint32_t mask, float lambda,
+                                        float shift, float *out_dev, void *hip_stream)
+{
+    if (!h) return rk_fail(ROCKET_EINVAL, "rocket_transform_noalloc: NULL handle");
+    const size_t need = rocket_workspace_bytes(h, B, mask, 0);
+    if (need == 0) return rk_fail(ROCKET_EINVAL, "rocket_transform_noalloc: B must be >= 1 and the feature mask a non-empty subset of 7");
+    if (need > kResidentScratchBytes)
+        return rk_fail(ROCKET_EWORKSPACE, "rocket_transform_noalloc: this batch needs a workspace of " + std::to_string(need) +
+                       " bytes, the resident one holds " + std::to_string(kResidentScratchBytes) +
+                       "; use rocket_transform with a workspace of the caller's");
+    if (!h->d_blob || h->params_dirty)
+        return rk_fail(ROCKET_EINVAL, "rocket_transform_noalloc: the kernels' parameters are not on the device yet; one "
+                       "earlier rocket_transform call on the handle uploads them");
+    void *ws = nullptr;
+    const int rc = resident_scratch(&ws);
+    if (rc != ROCKET_OK) return rc;
+    return transform_impl("rocket_transform_noalloc", h, x_dev, false, B, mask, lambda, shift, out_dev, ws,
+                          kResidentScratchBytes, hip_stream, true);
 }
 
 extern "C" int rocket_infer(rocket_kernels *h, const void *x_dev, int x_is_u8, int32_t B, uint32_t mask, float lambda,

@@ -20,7 +20,7 @@ LIB_PATH = os.environ.get("ROCKET_LIB") or os.path.join(_HERE, "librocket_mi355x
 EXPORTS = [
     "rocket_make_kernels", "rocket_kernels_import", "rocket_kernels_view_get",
     "rocket_kernels_set_params", "rocket_num_features", "rocket_workspace_bytes",
-    "rocket_transform", "rocket_soft_ppv_backward", "rocket_transform_u8", "rocket_soft_ppv_backward_u8",
+    "rocket_transform", "rocket_transform_noalloc", "rocket_soft_ppv_backward", "rocket_transform_u8", "rocket_soft_ppv_backward_u8",
     "rocket_work_per_series", "rocket_jobs_view_get",
     "rocket_profile_enable", "rocket_profile_read", "rocket_calibrate_fma",
     "rocket_ridge_workspace_bytes", "rocket_ridge_fit", "rocket_ridge_predict", "rocket_infer",
@@ -70,6 +70,7 @@ def load_library():
     lib.rocket_workspace_bytes.argtypes = [vp, i32, u32, C.c_int]
     lib.rocket_workspace_bytes.restype = C.c_size_t
     lib.rocket_transform.argtypes = [vp, vp, i32, u32, f32, f32, vp, vp, C.c_size_t, vp]
+    lib.rocket_transform_noalloc.argtypes = [vp, vp, i32, u32, f32, f32, vp, vp]
     lib.rocket_soft_ppv_backward.argtypes = [vp, vp, i32, u32, vp, f32, f32, C.c_int, vp, vp, vp, C.c_size_t, vp]
     lib.rocket_transform_u8.argtypes = lib.rocket_transform.argtypes
     lib.rocket_soft_ppv_backward_u8.argtypes = lib.rocket_soft_ppv_backward.argtypes
@@ -256,6 +257,23 @@ def rocket_transform(kernels, x, feature_mask, lam=10.0, shift=-3.0, out=None, w
     _check(getattr(load_library(), _entry)(
         kernels.handle, x.data_ptr(), B, feature_mask, lam, shift, out.data_ptr(),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(torch, stream)))
+    return out
+
+
+def rocket_transform_noalloc(kernels, x, feature_mask, out, lam=10.0, shift=-3.0, stream=None):
+    """rocket_transform into `out` (float32 CUDA, (B, F*K)) with the library's resident workspace:
+    nothing is allocated, here or in the library."""
+    torch = _torch()
+    if not (x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() == 3):
+        raise RocketError(ROCKET_EINVAL, "x must be a contiguous float32 CUDA tensor of shape (B, C, L)")
+    B = x.shape[0]
+    if x.shape[1] != kernels.C or x.shape[2] != kernels.L:
+        raise RocketError(ROCKET_ESHAPE, "x does not match the kernels' (C, L)")
+    F = rocket_num_features(feature_mask)
+    if not (out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and tuple(out.shape) == (B, F * kernels.K)):
+        raise RocketError(ROCKET_EINVAL, "out must be a contiguous float32 CUDA tensor of shape (B, F*K)")
+    _check(load_library().rocket_transform_noalloc(kernels.handle, x.data_ptr(), B, feature_mask, lam, shift,
+                                                   out.data_ptr(), _stream_ptr(torch, stream)))
     return out
 
 

@@ -140,6 +140,16 @@ def test_argument_validation_without_gpu():
     args = (h.handle, dummy, 0, 4, 5, 10.0, -3.0, dummy, dummy, dummy, 0.1, 0, dummy, dummy, 16, None)
     assert lib.rocket_train_step(*args) == rocket.ROCKET_EWORKSPACE
     assert lib.rocket_kernels_subset(h.handle, None, 1, ctypes.byref(ctypes.c_void_p())) == E
+    # the entry point that allocates nothing: bad sizes, then a handle whose parameters were never uploaded
+    assert lib.rocket_transform_noalloc(None, dummy, 1, 3, 10.0, -3.0, dummy, None) == E
+    assert lib.rocket_transform_noalloc(h.handle, dummy, 0, 3, 10.0, -3.0, dummy, None) == E
+    assert lib.rocket_transform_noalloc(h.handle, dummy, 1, 8, 10.0, -3.0, dummy, None) == E
+    assert lib.rocket_transform_noalloc(h.handle, dummy, 1, 3, 10.0, -3.0, dummy, None) == E
+    assert "upload" in rocket.rocket_last_error()
+    assert rocket.rocket_workspace_bytes(h, 100000, 3) > 64 << 20
+    assert lib.rocket_transform_noalloc(h.handle, dummy, 100000, 3, 10.0, -3.0, dummy, None) == rocket.ROCKET_EWORKSPACE
+    assert lib.rocket_jobs_view_get(h.handle, None, None, None, None, None, None) == E
+    assert lib.rocket_calibrate_fma(None, None) == E
     h.free()
     rocket.load_library().rocket_free_kernels(None)
 
