@@ -10,6 +10,8 @@ LIB = os.path.join(HERE, "librocket_mi355x.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall"]
+COMMON += os.environ.get("ROCKET_EXTRA_FLAGS", "").split()      # e.g. -DRK_TILE_POSITIONS=32768 for tuning runs
+LIB = os.environ.get("ROCKET_LIB_OUT", LIB)
 # device code: gfx950 only; packed-FP32 instruction selection is switched off
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -200,7 +200,10 @@ __device__ __forceinline__ void rk_forward_body(const KernelCtx &k, int nout, co
             left -= nb * R;
         }
     };
-#if RK_RMAX == 32
+#if RK_RMAX >= 64
+    bands_of(std::integral_constant<int, 64>{}, false);
+#endif
+#if RK_RMAX >= 32
     bands_of(std::integral_constant<int, 32>{}, false);
 #endif
     bands_of(std::integral_constant<int, 16>{}, false);
