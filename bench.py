@@ -1,15 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the ROCKET transform hot path on one MI355X.
 
-A step is one rocket_transform call (zero-pad copy + conv/pooling kernel) on
+A step is one rocket_transform call (zero-pad copy + conv/pooling kernel + feature kernel) on
 the paper's headline workload: a batch of 64 examples of 20 channels x 50,000
 timesteps through K = 10,000 random kernels, two pooled features per kernel
 (max + PPV).  Inputs are synthetic (seeded AR(1) channels, z-normalised) and
-resident in HBM before the timed region.  Prints one JSON line.
+resident in HBM before the timed region.  Prints one JSON line; the default run also
+carries the other workloads (univariate series/s, forward + backward, long series) as
+sub-records, each timed the same way.
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -20,18 +23,23 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X datasheet, packed FP32 on the vector ALUs
-# HBM-side bytes per launch of the dominant kernel, from the two `rocprofv3 --pmc` runs (FETCH_SIZE,
-# WRITE_SIZE, each scaled by what the counter reads for the padding copy of known size) whose summaries
-# are under profiles/: (workload, batch, feature mask) -> bytes.  Other shapes report null.
+# Memory-side bytes per launch of the dominant kernel.  These are not measured by this program: they come
+# from `rocprofv3 --pmc` runs of this same command whose summaries are under profiles/ (the file and the
+# commit it was taken on are repeated in the JSON line).  `l2_fill` = FETCH_SIZE + WRITE_SIZE (traffic between
+# L2 and the fabric: Infinity Cache hits and DRAM together), each scaled by what the counter reads for the
+# padding copy of known size; `dram` = TCC_EA0_RDREQ_DRAM / TCC_EA0_WRREQ_DRAM requests scaled the same way.
+# (workload, batch, feature mask) -> figures; other shapes report null.
 MEASURED_TRAFFIC = {
-    # profiles/rk_forward_multivariate-20x50k.md: 12,581,194 KiB x 1.968 fetched + 59,074 KiB x 1.001 written
-    ("multivariate-20x50k", 64, 3): 25414576462,
-    # profiles/rk_backward_multivariate-20x50k-grad.md: 20,025,199 KiB x 1.968 + 168,805 KiB x 1.001
-    ("multivariate-20x50k-grad", 60, 5): 40528449964,
+    ("multivariate-20x50k", 64, 3): {
+        "l2_fill_bytes": 25414576462, "dram_bytes": None,
+        "source": "profiles/rk_forward_multivariate-20x50k.md", "commit": "8f98765"},
+    ("multivariate-20x50k-grad", 60, 5): {
+        "l2_fill_bytes": 40528449964, "dram_bytes": None,
+        "source": "profiles/rk_backward_multivariate-20x50k-grad.md", "commit": "3bc96d2"},
 }
 
 WORKLOADS = {
-    # name: (synth config, feature mask or None = the config's, description)
+    # name: synth config
     "multivariate-20x50k": 2,
     "multivariate-20x50k-grad": 3,
     "multivariate-20x50k-train": 3,   # whole training step: transform, linear head, loss gradient, backward, update
@@ -54,7 +62,7 @@ def parse():
     ap.add_argument("--lam", type=float, default=10.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--lean", action="store_true",
-                    help="only the timed region: no extra workloads, no H2D-inclusive run, no FMA calibration "
+                    help="only the timed region: no extra workloads, no H2D-inclusive run, no unit calibration "
                          "(for profiler runs, so that the trace holds the timed launches only)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time its replays (for launch-bound small workloads)")
@@ -62,7 +70,7 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(cfg_id, x_host, kr, mask, lam, n_examples):
+def cpu_baseline(x_host, kr, lam, n_examples):
     """Times the oracle (all host threads) on the first n_examples examples x all kernels."""
     import oracle
     xs = x_host[:n_examples]
@@ -78,26 +86,143 @@ def cpu_baseline(cfg_id, x_host, kr, mask, lam, n_examples):
     }
 
 
-def quick_rate(rocket, synth, torch, cfg_id, lam, steps=20, warmup=3):
-    """series/s and conv TFLOP/s of a small workload, whole batch resident, same timing rules."""
-    cfg = synth.CONFIGS[cfg_id]
-    B, mask = cfg["B"], cfg["features"]
-    h = rocket.rocket_make_kernels(synth.seed_k(cfg_id), cfg["K"], cfg["C"], cfg["L"])
-    fma, _ = rocket.rocket_work_per_series(h)
-    x = torch.from_numpy(synth.make_input(cfg_id)).cuda()
-    out = torch.empty((B, rocket.rocket_num_features(mask) * cfg["K"]), dtype=torch.float32, device="cuda")
-    ws = torch.empty(rocket.rocket_workspace_bytes(h, B, mask), dtype=torch.uint8, device="cuda")
-    for _ in range(warmup):
-        rocket.rocket_transform(h, x, mask, lam, -3.0, out=out, workspace=ws)
+def time_steps(torch, run, steps):
+    """Runs `steps` steps between two device synchronisations.  Returns the wall-clock seconds of the whole
+    region (what the headline rate is computed from) and the per-step milliseconds from events recorded on the
+    current stream around every step (median and minimum are taken from those)."""
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(steps):
-        rocket.rocket_transform(h, x, mask, lam, -3.0, out=out, workspace=ws)
+    marks[0].record()
+    for i in range(steps):
+        run()
+        marks[i + 1].record()
     torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / steps
-    h.free()
-    return {"workload": cfg["name"], "B": B, "C": cfg["C"], "L": cfg["L"], "K": cfg["K"], "features": mask,
-            "value": B / dt, "unit": "series/s", "ms_per_step": 1e3 * dt, "conv_tflops": 2.0 * fma * B / dt / 1e12}
+    elapsed = time.perf_counter() - t0
+    per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
+    return elapsed, per_step
+
+
+class Workload:
+    """One workload set up on the device: kernels, resident input, outputs, workspace, and its step."""
+
+    def __init__(self, torch, rocket, synth, name, lam, batch=None, features=None):
+        self.torch, self.rocket, self.name, self.lam = torch, rocket, name, lam
+        self.cfg_id = WORKLOADS[name]
+        cfg = synth.CONFIGS[self.cfg_id]
+        self.B = cfg["B"] if batch is None else batch
+        self.mask = cfg["features"] if features is None else features
+        self.K, self.C, self.L = cfg["K"], cfg["C"], cfg["L"]
+        self.from_u8 = name.endswith("-u8")
+        self.train = name.endswith("-train")
+        self.with_grad = self.cfg_id == 3
+        self.x_host = synth.make_input_u8(self.cfg_id, B=self.B) if self.from_u8 else synth.make_input(self.cfg_id, B=self.B)
+        self.h = rocket.rocket_make_kernels(synth.seed_k(self.cfg_id), self.K, self.C, self.L)
+        self.fma_per_series, self.outputs_per_series = rocket.rocket_work_per_series(self.h)
+        self.F = rocket.rocket_num_features(self.mask)
+        dev = torch.device("cuda:0")
+        self.x = torch.from_numpy(self.x_host).to(dev)
+        self.out = torch.empty((self.B, self.F * self.K), dtype=torch.float32, device=dev)
+        self.ws = torch.empty(rocket.rocket_workspace_bytes(self.h, self.B, self.mask, self.with_grad),
+                              dtype=torch.uint8, device=dev)
+        self.stream = torch.cuda.current_stream()
+        if self.with_grad:
+            # forward (max + softPPV), then the backward pass from a seeded N(0,1) upstream gradient
+            self.gout = torch.from_numpy(synth.make_upstream_grad(self.cfg_id, self.B, self.F * self.K)).to(dev)
+            self.gw = torch.empty(self.h.total_weights, dtype=torch.float32, device=dev)
+            self.gb = torch.empty(self.K, dtype=torch.float32, device=dev)
+        if self.train:
+            # a fixed random linear head and roughness-like targets; a small learning rate, re-centred rows
+            rng = np.random.Generator(np.random.PCG64(synth.seed_g(self.cfg_id)))
+            self.coef = torch.from_numpy(rng.standard_normal(self.F * self.K) * 0.01).to(dev)
+            self.icpt = torch.tensor([1.2], dtype=torch.float64, device=dev)
+            self.targets = torch.from_numpy((0.6 + 1.2 * rng.random(self.B)).astype(np.float32)).to(dev)
+            self.train_ws = torch.empty(rocket.rocket_train_workspace_bytes(self.h, self.B, self.mask),
+                                        dtype=torch.uint8, device=dev)
+        self.transform = rocket.rocket_transform_u8 if self.from_u8 else rocket.rocket_transform
+
+    def backward(self):
+        self.rocket.rocket_soft_ppv_backward(self.h, self.x, self.mask, self.gout, self.lam, -3.0, True,
+                                             grad_w=self.gw, grad_b=self.gb, workspace=self.ws, stream=self.stream)
+
+    def step(self):
+        if self.train:
+            self.rocket.rocket_train_step(self.h, self.x, self.mask, self.coef, self.icpt, self.targets, 1e-3,
+                                          self.lam, -3.0, True, workspace=self.train_ws, stream=self.stream)
+            return
+        self.transform(self.h, self.x, self.mask, self.lam, -3.0, out=self.out, workspace=self.ws, stream=self.stream)
+        if self.with_grad:
+            self.backward()
+
+    def kernel_time(self, steps):
+        """Average duration (ms) of the dominant kernel over `steps` launches, from the HIP events the library
+        records on the call's stream around that kernel (the backward kernel for the gradient workloads)."""
+        self.rocket.rocket_profile_enable(self.h, True)
+        for _ in range(steps):
+            if self.with_grad:
+                self.backward()
+            else:
+                self.transform(self.h, self.x, self.mask, self.lam, -3.0, out=self.out, workspace=self.ws,
+                               stream=self.stream)
+        self.torch.cuda.synchronize()
+        launches, ms = self.rocket.rocket_profile_read(self.h)
+        self.rocket.rocket_profile_enable(self.h, False)
+        assert launches == steps
+        return ms / launches
+
+    def roofline(self, kernel_ms):
+        # conv FMAs only, as the method defines them; the backward kernel recomputes the conv
+        # and does as many multiply-adds again for the weight gradient
+        flops = 2.0 * self.fma_per_series * self.B * (2.0 if self.with_grad else 1.0)
+        achieved = flops / (kernel_ms * 1e-3) / 1e12
+        # pooling, counted as the method defines it: max 1, PPV 2 (compare, add), softPPV 6
+        # (fma = 2, exp, add, rcp, add) flop per position; the backward kernel's sigmoid derivative 10
+        pool_per_pos = (1 if self.mask & 1 else 0) + (2 if self.mask & 2 else 0) + (6 if self.mask & 4 else 0)
+        pool_flops = self.outputs_per_series * self.B * (10.0 if self.with_grad else pool_per_pos)
+        traffic = MEASURED_TRAFFIC.get((self.name, self.B, self.mask))
+        r = {
+            "bound": "alu", "achieved": achieved, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": achieved / FP32_VECTOR_PEAK_TFLOPS,
+            "traffic": traffic["l2_fill_bytes"] if traffic else None,
+            "kernel": "rk_backward" if self.with_grad else ("rk_forward<64>" if self.L <= 8192 else "rk_forward<256>"),
+            "kernel_ms": kernel_ms, "flop_per_launch": flops, "fma_per_example": self.fma_per_series,
+            "pooled_positions_per_example": self.outputs_per_series,
+            "achieved_with_pooling": (flops + pool_flops) / (kernel_ms * 1e-3) / 1e12,
+        }
+        if traffic:
+            # traffic is the figure of an earlier profiler run, not of this run (see MEASURED_TRAFFIC)
+            r["traffic_kind"] = "L2 fill (Infinity Cache + DRAM), from " + traffic["source"] + " @ " + traffic["commit"]
+            r["l2_fill_GBps"] = traffic["l2_fill_bytes"] / (kernel_ms * 1e-3) / 1e9
+            r["dram_bytes"] = traffic["dram_bytes"]
+            r["dram_GBps"] = traffic["dram_bytes"] / (kernel_ms * 1e-3) / 1e9 if traffic["dram_bytes"] else None
+        return r
+
+    def free(self):
+        self.h.free()
+
+
+def sub_record(torch, rocket, synth, name, lam, min_steps=10, min_seconds=2.0, max_steps=400):
+    """A secondary workload timed like the main one: at least `min_steps` steps and `min_seconds` seconds
+    (short steps are repeated up to `max_steps` times), mean / median / minimum, and its own roofline."""
+    w = Workload(torch, rocket, synth, name, lam)
+    for _ in range(3):
+        w.step()
+    torch.cuda.synchronize()
+    elapsed, per_step = time_steps(torch, w.step, min_steps)
+    more = int(min(max_steps, np.ceil(min_seconds / (elapsed / min_steps)))) - min_steps
+    if more > 0:
+        e2, p2 = time_steps(torch, w.step, more)
+        elapsed, per_step = elapsed + e2, per_step + p2
+    steps = len(per_step)
+    kernel_ms = w.kernel_time(min(steps, 10))
+    unit = "series/s" if w.cfg_id in (0, 1) else "examples/s"
+    rec = {"workload": name, "B": w.B, "C": w.C, "L": w.L, "K": w.K, "features": w.mask,
+           "what": "forward + softPPV backward (max sub-gradient included)" if w.with_grad else "forward",
+           "value": w.B * steps / elapsed, "unit": unit, "steps": steps, "ms_per_step": 1e3 * elapsed / steps,
+           "ms_per_step_median": statistics.median(per_step), "ms_per_step_min": min(per_step),
+           "roofline": w.roofline(kernel_ms)}
+    w.free()
+    return rec
 
 
 def ridge_bench(args, torch, rocket):
@@ -115,16 +240,13 @@ def ridge_bench(args, torch, rocket):
 
     for _ in range(args.warmup):
         step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / args.steps
+    elapsed, per_step = time_steps(torch, step, args.steps)
+    dt = elapsed / args.steps
     print(json.dumps({
         "metric": "ridge fits/sec (677 x 20,000, fp64, dual form) with a 64-row predict each",
         "value": 1.0 / dt, "unit": "fits/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": 1e3 * dt, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": 1e3 * dt, "ms_per_step_median": statistics.median(per_step), "ms_per_step_min": min(per_step),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": args.workload, "n": n, "p": p, "predict_rows": m, "alpha": 1.0},
     }))
@@ -137,7 +259,6 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
     import synth
     from paper_2301_08527_amd import rocket
@@ -149,154 +270,79 @@ def main():
     if args.workload == "ridge-677x20000":
         ridge_bench(args, torch, rocket)
         return
-    cfg_id = WORKLOADS[args.workload]
-    cfg = synth.CONFIGS[cfg_id]
-    B = cfg["B"] if args.batch is None else args.batch
-    mask = cfg["features"] if args.features is None else args.features
-    K, C, L = cfg["K"], cfg["C"], cfg["L"]
-
-    from_u8 = args.workload.endswith("-u8")
-    x_host = synth.make_input_u8(cfg_id, B=B) if from_u8 else synth.make_input(cfg_id, B=B)
-    h = rocket.rocket_make_kernels(synth.seed_k(cfg_id), K, C, L)
-    fma_per_series, outputs_per_series = rocket.rocket_work_per_series(h)
-    F = rocket.rocket_num_features(mask)
-
-    dev = torch.device("cuda:0")
-    x = torch.from_numpy(x_host).to(dev)
-    out = torch.empty((B, F * K), dtype=torch.float32, device=dev)
-    ws = torch.empty(rocket.rocket_workspace_bytes(h, B, mask), dtype=torch.uint8, device=dev)
-    stream = torch.cuda.current_stream()
-
-    with_grad = cfg_id == 3
-    if with_grad:
-        # forward (max + softPPV), then the backward pass from a seeded N(0,1) upstream gradient
-        view = rocket.rocket_kernels_view_get(h)
-        gout = torch.from_numpy(synth.make_upstream_grad(cfg_id, B, F * K)).to(dev)
-        gw = torch.empty(len(view["weights"]), dtype=torch.float32, device=dev)
-        gb = torch.empty(K, dtype=torch.float32, device=dev)
-        ws = torch.empty(rocket.rocket_workspace_bytes(h, B, mask, True), dtype=torch.uint8, device=dev)
-
-    def backward():
-        rocket.rocket_soft_ppv_backward(h, x, mask, gout, args.lam, -3.0, True, grad_w=gw, grad_b=gb,
-                                        workspace=ws, stream=stream)
-
-    transform = rocket.rocket_transform_u8 if from_u8 else rocket.rocket_transform
-
-    train = args.workload.endswith("-train")
-    if train:
-        # a fixed random linear head and roughness-like targets; a small learning rate, re-centred rows
-        rng = np.random.Generator(np.random.PCG64(synth.seed_g(cfg_id)))
-        coef = torch.from_numpy(rng.standard_normal(F * K) * 0.01).to(dev)
-        icpt = torch.tensor([1.2], dtype=torch.float64, device=dev)
-        targets = torch.from_numpy((0.6 + 1.2 * rng.random(B)).astype(np.float32)).to(dev)
-        train_ws = torch.empty(rocket.rocket_train_workspace_bytes(h, B, mask), dtype=torch.uint8, device=dev)
-
-    def step():
-        if train:
-            rocket.rocket_train_step(h, x, mask, coef, icpt, targets, 1e-3, args.lam, -3.0, True,
-                                     workspace=train_ws, stream=stream)
-            return
-        transform(h, x, mask, args.lam, -3.0, out=out, workspace=ws, stream=stream)
-        if with_grad:
-            backward()
+    w = Workload(torch, rocket, synth, args.workload, args.lam, args.batch, args.features)
+    cfg_id, B, mask, K, C, L = w.cfg_id, w.B, w.mask, w.K, w.C, w.L
 
     for _ in range(args.warmup):
-        step()
+        w.step()
     torch.cuda.synchronize()
 
-    run = step
+    run = w.step
     if args.graph:
         # the parameters are on the device after the warm-up: a step only launches kernels
         side = torch.cuda.Stream()
-        stream = side
+        w.stream = side
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
-            step()
+            w.step()
         run = graph.replay
         run()
         torch.cuda.synchronize()
-        stream = torch.cuda.current_stream()
+        w.stream = torch.cuda.current_stream()
 
-    rocket.rocket_profile_enable(h, not with_grad and not args.graph)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    if args.graph and not with_grad:
-        # kernel time for the roofline figure: eager launches after the timed region
-        rocket.rocket_profile_enable(h, True)
-        for _ in range(args.steps):
-            step()
-        torch.cuda.synchronize()
-    if with_grad:
-        # the dominant kernel of this workload is the backward one: time it alone, after the timed region
-        rocket.rocket_profile_enable(h, True)
-        for _ in range(args.steps):
-            backward()
-        torch.cuda.synchronize()
-    launches, kernel_ms = rocket.rocket_profile_read(h)
-    rocket.rocket_profile_enable(h, False)
-    assert launches == args.steps
+    elapsed, per_step = time_steps(torch, run, args.steps)
+    # duration of the dominant kernel: eager launches after the timed region, HIP events on their stream
+    kernel_ms_avg = w.kernel_time(args.steps)
 
     ms_per_step = 1e3 * elapsed / args.steps
     value = B * args.steps / elapsed
-    kernel_ms_avg = kernel_ms / launches
-    # conv FMAs only, as the method defines them; the backward kernel recomputes the conv
-    # and does as many multiply-adds again for the weight gradient
-    flops_per_launch = 2.0 * fma_per_series * B * (2.0 if with_grad else 1.0)
-    achieved = flops_per_launch / (kernel_ms_avg * 1e-3) / 1e12
-    # pooling, counted as the method defines it: max 1, PPV 2 (compare, add), softPPV 6
-    # (fma = 2, exp, add, rcp, add) flop per position; the backward kernel's sigmoid derivative 10
-    pool_per_pos = (1 if mask & 1 else 0) + (2 if mask & 2 else 0) + (6 if mask & 4 else 0)
-    pool_flops = outputs_per_series * B * (10.0 if with_grad else pool_per_pos)
-    achieved_with_pooling = (flops_per_launch + pool_flops) / (kernel_ms_avg * 1e-3) / 1e12
-    plain_fma_ceiling = None if args.lean else rocket.rocket_calibrate_fma()
-    traffic = MEASURED_TRAFFIC.get((args.workload, B, mask))
+    roofline = w.roofline(kernel_ms_avg)
+    if not args.lean:
+        plain = rocket.rocket_calibrate_fma()
+        roofline["plain_fma_measured"] = plain
+        roofline["frac_of_plain_fma_measured"] = roofline["achieved"] / plain
+        roofline["units_measured"] = rocket.rocket_calibrate_units()
+    roofline["note"] = ("peak is the data-sheet figure, which assumes packed FP32; this build issues plain v_fma_f32, "
+                        "whose rate measured in this run by a kernel of nothing but FMAs is plain_fma_measured; "
+                        "units_measured are whole-device rates of the load, LDS and matrix units from micro-kernels")
 
     line = {
         "metric": ("examples/sec (20ch x 50k, K=10k) and % of FP32 vector peak" if cfg_id == 2 else
-                   "examples/sec, whole training step through softPPV (20ch x 50k, K=10k)" if train else
+                   "examples/sec, whole training step through softPPV (20ch x 50k, K=10k)" if w.train else
                    "examples/sec, forward + softPPV backward (20ch x 50k, K=10k)" if cfg_id == 3 else
                    "series/sec" if cfg_id in (0, 1) else "examples/sec"),
         "value": value, "unit": "examples/s" if cfg_id != 1 and cfg_id != 0 else "series/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_median": statistics.median(per_step), "ms_per_step_min": min(per_step),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "launch": "hip-graph replay" if args.graph else "eager", "B": B, "C": C, "L": L, "K": K, "features": mask,
-                   "lambda": args.lam, "shift": -3.0, "seed_x": synth.seed_x(cfg_id), "seed_k": synth.seed_k(cfg_id)},
-        "roofline": {
-            "bound": "alu", "achieved": achieved, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": achieved / FP32_VECTOR_PEAK_TFLOPS, "traffic": traffic,
-            "kernel": "rk_backward" if with_grad else "rk_forward", "kernel_ms": kernel_ms_avg,
-            "flop_per_launch": flops_per_launch, "fma_per_example": fma_per_series,
-            "pooled_positions_per_example": outputs_per_series,
-            "achieved_with_pooling": achieved_with_pooling,
-            "plain_fma_measured": plain_fma_ceiling,
-            "frac_of_plain_fma_measured": achieved / plain_fma_ceiling if plain_fma_ceiling else None,
-            "note": "peak is the data-sheet figure, which assumes packed FP32; this build issues plain v_fma_f32, "
-                    "whose rate measured in this run by a kernel of nothing but FMAs is plain_fma_measured",
-        },
-        "percent_of_fp32_vector_peak": 100.0 * achieved / FP32_VECTOR_PEAK_TFLOPS,
+        "config": {"workload": args.workload, "launch": "hip-graph replay" if args.graph else "eager", "B": B, "C": C,
+                   "L": L, "K": K, "features": mask, "lambda": args.lam, "shift": -3.0,
+                   "seed_x": synth.seed_x(cfg_id), "seed_k": synth.seed_k(cfg_id)},
+        "roofline": roofline,
+        "percent_of_fp32_vector_peak": 100.0 * roofline["achieved"] / FP32_VECTOR_PEAK_TFLOPS,
     }
 
-    if traffic:
-        line["roofline"]["hbm_GBps"] = traffic / (kernel_ms_avg * 1e-3) / 1e9
-    if cfg_id == 2 and not from_u8 and not args.lean:
-        # the univariate workloads of the classic ROCKET setting, in series/s, in the same run
-        line["series_per_s"] = [quick_rate(rocket, synth, torch, i, args.lam) for i in (1, 0)]
+    main_run = cfg_id == 2 and not w.from_u8 and not args.lean and args.batch is None and args.features is None
+    if main_run:
+        # the other workloads, each timed for at least 10 steps and 2 seconds: the univariate ones of the classic
+        # ROCKET setting in series/s, the forward + backward step and the long-series stress in examples/s
+        line["series_per_s"] = [sub_record(torch, rocket, synth, n, args.lam) for n in ("univariate-standard", "univariate-tiny")]
+        line["fwd_bwd"] = sub_record(torch, rocket, synth, "multivariate-20x50k-grad", args.lam)
+        line["long"] = sub_record(torch, rocket, synth, "long-20x200k", args.lam)
 
-    if cfg_id == 2 and not train and not args.lean:
+    if cfg_id == 2 and not w.train and not args.lean:
         # once with the host-to-device copy of the batch inside the timed region (pinned source)
-        x_pin = torch.from_numpy(x_host).pin_memory()
+        x, ws, out = w.x, w.ws, w.out
+        x_pin = torch.from_numpy(w.x_host).pin_memory()
         for _ in range(2):
             x.copy_(x_pin, non_blocking=True)
-            step()
+            w.step()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
             x.copy_(x_pin, non_blocking=True)
-            step()
+            w.step()
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / args.steps
         line["with_h2d_copy"] = {"value": B / dt, "unit": "examples/s", "ms_per_step": 1e3 * dt,
@@ -321,7 +367,7 @@ def main():
                     copied[s].record(copy_stream)
                 with torch.cuda.stream(work_stream):
                     work_stream.wait_event(copied[s])
-                    transform(h, xs[s], mask, args.lam, -3.0, out=outs[s], workspace=wss[s], stream=work_stream)
+                    w.transform(w.h, xs[s], mask, args.lam, -3.0, out=outs[s], workspace=wss[s], stream=work_stream)
                     used[s].record(work_stream)
             torch.cuda.synchronize()
 
@@ -331,25 +377,25 @@ def main():
         dt = (time.perf_counter() - t0) / args.steps
         line["with_h2d_copy"]["overlapped"] = {"value": B / dt, "unit": "examples/s", "ms_per_step": 1e3 * dt}
 
-    if not args.no_cpu_baseline and not with_grad:
-        kr = rocket.rocket_kernels_view_get(h)
+    if not args.no_cpu_baseline and not w.with_grad:
+        import oracle
+        # the oracle computes with kernels from its own sampler (bit-identical to the library's, as the tests check)
+        kr = oracle.sample_kernels(synth.seed_k(cfg_id), K, C, L)
         n_ex = args.cpu_examples
         if n_ex is None:
             # aim at 10-30 s of oracle time: the oracle does roughly 1.4 GFMA/s per thread
-            import oracle
             rate = 1.4e9 * oracle.num_threads()
-            n_ex = int(max(1, min(B, round(15.0 * rate / fma_per_series))))
-        line["cpu_baseline"] = cpu_baseline(cfg_id, x_host, kr, mask, args.lam, n_ex)
+            n_ex = int(max(1, min(B, round(15.0 * rate / w.fma_per_series))))
+        line["cpu_baseline"] = cpu_baseline(w.x_host, kr, args.lam, n_ex)
         # the same oracle on one core, on a sample that takes about 10 s
-        import oracle
         threads = oracle.num_threads()
         oracle.set_threads(1)
-        one = cpu_baseline(cfg_id, x_host, kr, mask, args.lam, int(max(1, round(10.0 * 1.4e9 / fma_per_series))))
+        one = cpu_baseline(w.x_host, kr, args.lam, int(max(1, round(10.0 * 1.4e9 / w.fma_per_series))))
         oracle.set_threads(threads)
         line["cpu_baseline"]["one_core"] = {"value": one["value"], "unit": one["unit"], "sample": one["sample"]}
 
     print(json.dumps(line))
-    h.free()
+    w.free()
 
 
 if __name__ == "__main__":

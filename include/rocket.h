@@ -239,6 +239,27 @@ int rocket_profile_read(rocket_kernels *kernels, int32_t *launches, double *tota
 int rocket_calibrate_fma(double *tflops, void *hip_stream);
 
 /*
+ * Measured rates of the other units that can bound the transform's kernels on the current device, one
+ * micro-kernel per unit, for the roofline discussion (which unit stops a kernel).  out (host, at least
+ * ROCKET_CAL_COUNT doubles) receives, by index:
+ *   ROCKET_CAL_LOAD_B32_L1       GB/s of 4-byte buffer loads into registers, every CU re-reading 4 KB (L1 hits)
+ *   ROCKET_CAL_LOAD_B32_L2       the same from 64 regions of 1 MB (L1 misses, L2 hits)
+ *   ROCKET_CAL_LOAD_B128_L1/_L2  the two as 16-byte loads
+ *   ROCKET_CAL_LOAD_B128_TO_LDS  GB/s of 16-byte buffer loads that write LDS directly (L2 hits)
+ *   ROCKET_CAL_LDS_READ_B32      GB/s of 4-byte LDS reads without bank conflicts
+ *   ROCKET_CAL_MFMA_F32_4X4X1    TFLOP/s of the 4x4x1 FP32 matrix instruction (all its multiply-adds counted)
+ *   ROCKET_CAL_MFMA_VALU_SERIAL  time of matrix wavefronts and vector-FMA wavefronts run together, divided by
+ *                                the sum of their times run alone: 1 = the two pipes do not overlap, 0.5 = fully
+ * All rates are whole-device.  Takes some tens of milliseconds; allocates and frees 64 MB of device memory.
+ */
+enum {
+    ROCKET_CAL_LOAD_B32_L1 = 0, ROCKET_CAL_LOAD_B32_L2 = 1, ROCKET_CAL_LOAD_B128_L1 = 2, ROCKET_CAL_LOAD_B128_L2 = 3,
+    ROCKET_CAL_LOAD_B128_TO_LDS = 4, ROCKET_CAL_LDS_READ_B32 = 5, ROCKET_CAL_MFMA_F32_4X4X1 = 6,
+    ROCKET_CAL_MFMA_VALU_SERIAL = 7, ROCKET_CAL_COUNT = 8
+};
+int rocket_calibrate_units(double *out, int32_t count, void *hip_stream);
+
+/*
  * Ridge regressor on the pooled features (paper section 3 part (3), section 3.3):
  * minimises ||y - X w - b||^2 + alpha ||w||^2 over (w, b), the intercept b unpenalised.
  * features_dev: device, n x p float32 row-major (the transform's output for n series);

@@ -62,3 +62,204 @@ extern "C" int rocket_calibrate_fma(double *tflops, void *hip_stream)
     *tflops = flop / (static_cast<double>(ms) * 1e-3) / 1e12;
     return ROCKET_OK;
 }
+
+
+// ------------------------------------------------------------------ the other units
+//
+// Rates of the units that bound the transform's kernels, measured with kernels that use one unit each:
+// buffer loads into registers from a footprint that stays in a CU's L1 and from one that streams out of L2,
+// the same as 16-byte loads, 16-byte loads that write LDS directly, LDS reads, and the FP32 matrix
+// instruction with the smallest tile (4x4x1, 16 blocks), alone and beside vector multiply-adds.
+
+namespace {
+
+typedef float rk_f4 __attribute__((ext_vector_type(4)));
+typedef int rk_i4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void *rk_lds_ptr;
+
+constexpr int kLoadGroups = 256 * 6;     // workgroups of 256 lanes
+constexpr int kLoadIters = 1500;
+constexpr int kRowsPerIter = 16;         // dword loads per lane and iteration (4 as 16-byte loads)
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rk_cal_buffer(const void *p, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, static_cast<int>(bytes), 0x00020000);
+}
+
+// Every workgroup reads `region_bytes` bytes over and over, block b the region b % nregions; one region of a
+// few KB stays in L1, many regions of 1 MB stream out of L2.  W = dwords per lane and load.
+template <int W>
+__global__ __launch_bounds__(256) void rk_cal_loads(const float *base, unsigned region_bytes, unsigned nregions, int iters,
+                                                    float *sink)
+{
+    constexpr int NL = kRowsPerIter / W;
+    const unsigned lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const __amdgpu_buffer_rsrc_t r =
+        rk_cal_buffer(reinterpret_cast<const char *>(base) + static_cast<size_t>(blockIdx.x % nregions) * region_bytes, region_bytes);
+    const unsigned rowb = 256u * W, voff = lane * 4u * W;
+    unsigned so = (wave * NL * rowb) % region_bytes;
+    float acc = 0.f;
+    for (int it = 0; it < iters; ++it) {
+        float v[NL * W];
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            unsigned s = so + i * rowb;
+            if (s >= region_bytes) s -= region_bytes;
+            if constexpr (W == 1) {
+                v[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, s, 0));
+            } else {
+                const rk_i4 q = __builtin_amdgcn_raw_buffer_load_b128(r, voff, s, 0);
+                v[4 * i] = __builtin_bit_cast(float, q.x); v[4 * i + 1] = __builtin_bit_cast(float, q.y);
+                v[4 * i + 2] = __builtin_bit_cast(float, q.z); v[4 * i + 3] = __builtin_bit_cast(float, q.w);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NL * W; ++i) acc += v[i];
+        so += NL * rowb;
+        while (so >= region_bytes) so -= region_bytes;
+    }
+    if (acc == 12345.678f) *sink = acc;
+}
+
+// 16-byte buffer loads with the LDS modifier: four per iteration and wavefront into the wavefront's own 4 KB of
+// LDS (lane l's 16 bytes land at byte 16*l of the 1 KB block the instruction names), then a wait for them.
+__global__ __launch_bounds__(256) void rk_cal_loads_to_lds(const float *base, unsigned region_bytes, unsigned nregions, int iters,
+                                                           float *sink)
+{
+    __shared__ __attribute__((aligned(16))) char slab[4][4096];
+    const unsigned lane = threadIdx.x & 63;
+    const unsigned wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const __amdgpu_buffer_rsrc_t r =
+        rk_cal_buffer(reinterpret_cast<const char *>(base) + static_cast<size_t>(blockIdx.x % nregions) * region_bytes, region_bytes);
+    unsigned so = (wave * 4096u) % region_bytes;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            unsigned s = so + i * 1024u;
+            if (s >= region_bytes) s -= region_bytes;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (rk_lds_ptr)(&slab[wave][i * 1024]), 16, lane * 16u, s, 0, 0);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        so += 4096u;
+        while (so >= region_bytes) so -= region_bytes;
+    }
+    if (iters < 0) *sink = *reinterpret_cast<const float *>(&slab[wave][lane * 4]);
+}
+
+// LDS reads, one dword per lane and read, consecutive lanes at consecutive words.
+__global__ __launch_bounds__(256) void rk_cal_lds_reads(int iters, float *sink)
+{
+    __shared__ float words[8192];
+    for (int i = threadIdx.x; i < 8192; i += 256) words[i] = static_cast<float>(i);
+    __syncthreads();
+    const unsigned lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float acc = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < kRowsPerIter; ++i) acc += words[(wave * 2048 + lane + i * 64 + it) & 8191u];
+    }
+    if (acc == 12345.678f) *sink = acc;
+}
+
+// mode 0: every wavefront issues the 4x4x1 FP32 matrix instruction on 8 independent accumulator tiles;
+// mode 1: even wavefronts do that, odd wavefronts run plain multiply-add chains; mode 2: only the even ones
+// work; mode 3: only the odd ones.
+__global__ __launch_bounds__(256) void rk_cal_matrix(int iters, float a0, float b0, int mode, float *sink)
+{
+    const unsigned wave = threadIdx.x >> 6;
+    const bool matrix_wave = mode == 0 || (wave & 1) == 0;
+    float s = 0.f;
+    if (matrix_wave) {
+        if (mode == 3) return;
+        rk_f4 acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = rk_f4{0.f, 0.f, 0.f, 0.f};
+        const float a = a0 + threadIdx.x * 1e-6f;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_4x4x1f32(a, b0, acc[i], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s += acc[i].x + acc[i].y + acc[i].z + acc[i].w;
+    } else {
+        if (mode == 2) return;
+        float v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = threadIdx.x * 0.001f + i;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) v[i] = fmaf(v[i], 0.999f, 0.001f);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += v[i];
+    }
+    if (s == 12345.678f) *sink = s;
+}
+
+}  // namespace
+
+extern "C" int rocket_calibrate_units(double *out, int32_t count, void *hip_stream)
+{
+    if (!out || count < ROCKET_CAL_COUNT) return rk_fail(ROCKET_EINVAL, "rocket_calibrate_units: out must hold ROCKET_CAL_COUNT values");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const size_t bytes = static_cast<size_t>(64) << 20;
+    float *buf = nullptr, *sink = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t err = hipMalloc(&buf, bytes);
+    if (err == hipSuccess) err = hipMalloc(&sink, 256);
+    if (err == hipSuccess) err = hipMemsetAsync(buf, 0, bytes, stream);
+    if (err == hipSuccess) err = hipEventCreate(&e0);
+    if (err == hipSuccess) err = hipEventCreate(&e1);
+    // runs `launch` twice (the first run warms caches and clocks) and returns the second run's milliseconds
+    auto timed = [&](auto launch, double &ms_out) {
+        if (err != hipSuccess) return;
+        launch();
+        err = hipEventRecord(e0, stream);
+        launch();
+        if (err == hipSuccess) err = hipEventRecord(e1, stream);
+        if (err == hipSuccess) err = hipEventSynchronize(e1);
+        float ms = 0.f;
+        if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
+        if (err == hipSuccess) err = hipGetLastError();
+        ms_out = ms;
+    };
+    const double load_bytes = 4.0 * kLoadGroups * kLoadIters * kRowsPerIter * 256.0;   // per launch, all wavefronts
+    double ms = 0.0;
+    auto gbps = [&](double b) { return ms > 0.0 ? b / (ms * 1e-3) / 1e9 : 0.0; };
+    timed([&] { hipLaunchKernelGGL((rk_cal_loads<1>), dim3(kLoadGroups), dim3(256), 0, stream, buf, 4096u, 1u, kLoadIters, sink); }, ms);
+    out[ROCKET_CAL_LOAD_B32_L1] = gbps(load_bytes);
+    timed([&] { hipLaunchKernelGGL((rk_cal_loads<1>), dim3(kLoadGroups), dim3(256), 0, stream, buf, 1u << 20, 64u, kLoadIters, sink); }, ms);
+    out[ROCKET_CAL_LOAD_B32_L2] = gbps(load_bytes);
+    timed([&] { hipLaunchKernelGGL((rk_cal_loads<4>), dim3(kLoadGroups), dim3(256), 0, stream, buf, 16384u, 1u, kLoadIters, sink); }, ms);
+    out[ROCKET_CAL_LOAD_B128_L1] = gbps(load_bytes);
+    timed([&] { hipLaunchKernelGGL((rk_cal_loads<4>), dim3(kLoadGroups), dim3(256), 0, stream, buf, 1u << 20, 64u, kLoadIters, sink); }, ms);
+    out[ROCKET_CAL_LOAD_B128_L2] = gbps(load_bytes);
+    timed([&] { hipLaunchKernelGGL(rk_cal_loads_to_lds, dim3(kLoadGroups), dim3(256), 0, stream, buf, 1u << 20, 64u, kLoadIters, sink); }, ms);
+    out[ROCKET_CAL_LOAD_B128_TO_LDS] = gbps(4.0 * kLoadGroups * kLoadIters * 4096.0);
+    timed([&] { hipLaunchKernelGGL(rk_cal_lds_reads, dim3(kLoadGroups), dim3(256), 0, stream, kLoadIters, sink); }, ms);
+    out[ROCKET_CAL_LDS_READ_B32] = gbps(load_bytes);
+    const int mgroups = 256 * 8, miters = 2000;
+    const double mflop = 64.0 * 512.0 * miters, vflop = 128.0 * 128.0 * miters;   // per wavefront: matrix / vector work
+    auto tflops = [&](double f) { return ms > 0.0 ? f / (ms * 1e-3) / 1e12 : 0.0; };
+    timed([&] { hipLaunchKernelGGL(rk_cal_matrix, dim3(mgroups), dim3(256), 0, stream, miters, 1.0001f, 0.5f, 0, sink); }, ms);
+    out[ROCKET_CAL_MFMA_F32_4X4X1] = tflops(mgroups * 4.0 * mflop);
+    timed([&] { hipLaunchKernelGGL(rk_cal_matrix, dim3(mgroups), dim3(256), 0, stream, miters, 1.0001f, 0.5f, 2, sink); }, ms);
+    const double ms_matrix_half = ms;
+    timed([&] { hipLaunchKernelGGL(rk_cal_matrix, dim3(mgroups), dim3(256), 0, stream, miters, 1.0001f, 0.5f, 3, sink); }, ms);
+    const double ms_vector_half = ms;
+    timed([&] { hipLaunchKernelGGL(rk_cal_matrix, dim3(mgroups), dim3(256), 0, stream, miters, 1.0001f, 0.5f, 1, sink); }, ms);
+    // 1 = the two kinds of wavefront take as long together as one after the other (no overlap); 0.5 would be full overlap
+    out[ROCKET_CAL_MFMA_VALU_SERIAL] = (ms_matrix_half + ms_vector_half) > 0.0 ? ms / (ms_matrix_half + ms_vector_half) : 0.0;
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (buf) (void)hipFree(buf);
+    if (sink) (void)hipFree(sink);
+    if (err != hipSuccess) return rk_fail(ROCKET_EHIP, std::string("rocket_calibrate_units: ") + hipGetErrorString(err));
+    return ROCKET_OK;
+}

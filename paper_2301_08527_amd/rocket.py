@@ -22,7 +22,7 @@ EXPORTS = [
     "rocket_kernels_set_params", "rocket_num_features", "rocket_workspace_bytes",
     "rocket_transform", "rocket_transform_noalloc", "rocket_soft_ppv_backward", "rocket_transform_u8", "rocket_soft_ppv_backward_u8",
     "rocket_work_per_series", "rocket_jobs_view_get",
-    "rocket_profile_enable", "rocket_profile_read", "rocket_calibrate_fma",
+    "rocket_profile_enable", "rocket_profile_read", "rocket_calibrate_fma", "rocket_calibrate_units",
     "rocket_ridge_workspace_bytes", "rocket_ridge_fit", "rocket_ridge_predict", "rocket_infer",
     "rocket_mse_grad", "rocket_sgd_update", "rocket_train_workspace_bytes", "rocket_train_step",
     "rocket_kernels_subset",
@@ -79,6 +79,7 @@ def load_library():
     lib.rocket_profile_enable.argtypes = [vp, C.c_int]
     lib.rocket_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]
     lib.rocket_calibrate_fma.argtypes = [C.POINTER(C.c_double), vp]
+    lib.rocket_calibrate_units.argtypes = [C.POINTER(C.c_double), i32, vp]
     lib.rocket_ridge_workspace_bytes.argtypes = [i32, i32]
     lib.rocket_ridge_workspace_bytes.restype = C.c_size_t
     lib.rocket_ridge_fit.argtypes = [vp, vp, i32, i32, C.c_double, vp, vp, vp, C.c_size_t, vp]
@@ -324,6 +325,18 @@ def rocket_calibrate_fma(stream=None):
     v = C.c_double()
     _check(load_library().rocket_calibrate_fma(C.byref(v), _stream_ptr(torch, stream)))
     return v.value
+
+
+CAL_NAMES = ("load_b32_l1_GBps", "load_b32_l2_GBps", "load_b128_l1_GBps", "load_b128_l2_GBps",
+             "load_b128_to_lds_GBps", "lds_read_b32_GBps", "mfma_f32_4x4x1_TFLOPs", "mfma_valu_serial_ratio")
+
+
+def rocket_calibrate_units(stream=None):
+    """Measured rates of the load, LDS and matrix units of the current device, keyed by CAL_NAMES."""
+    torch = _torch()
+    v = (C.c_double * len(CAL_NAMES))()
+    _check(load_library().rocket_calibrate_units(v, len(CAL_NAMES), _stream_ptr(torch, stream)))
+    return dict(zip(CAL_NAMES, list(v)))
 
 
 def rocket_ridge_workspace_bytes(n, p):
