@@ -334,6 +334,34 @@ int rocket_train_step(rocket_kernels *kernels, const void *x_dev, int x_is_u8, i
                       void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * MINIROCKET-style variant.  The paper describes MINIROCKET in its related-work section only (section 2) and
+ * names it as the extension to build next (section 6): two-valued kernels, so that the convolution needs
+ * additions only; weights from a predetermined set; biases sampled from the input data; PPV as the only
+ * pooled feature.  Everything the paragraph leaves open is this build's reading (parity with the original
+ * model is not claimed):
+ *
+ * rocket_minirocket_kernels: `groups` groups of 84 kernels of length 9.  The 84 are all weight rows with
+ * three weights of 2 and six of -1 (zero sum, like the mean-centred weights of section 3.1), in lexicographic
+ * order of the positions of the 2s; the same row applies to every channel of the kernel.  A group shares
+ * dilation, padding and channel subset, drawn by the laws of section 3.1 from the stream of (seed, group).
+ * Biases start at 0.  Host only.  Requires groups, C >= 1 and L >= 9.  K = 84 * groups.
+ *
+ * rocket_minirocket_fit_bias: kernel k draws, from the stream of (seed + 1, k), one of the B series of x_dev
+ * (device, B x C x L float32) and a level q in [0, 1); its bias becomes minus the order statistic of rank
+ * floor(q (n - 1)) (0-based, ascending) of its bias-free output on that series, so that on that series
+ * PPV = (n - 1 - rank) / n when the outputs are distinct.  Works on any handle.  The biases are written into
+ * the handle's device copy; the host copy follows on the next rocket_kernels_view_get (as after
+ * rocket_sgd_update).  workspace_dev: rocket_minirocket_fit_workspace_bytes(kernels, B) bytes, 256-byte
+ * aligned.  One-time set-up work, not tuned for speed; it synchronises hip_stream once.
+ *
+ * The features are rocket_transform with feature_mask = ROCKET_F_PPV: one PPV per kernel (Eq. 1-2).
+ */
+int rocket_minirocket_kernels(uint64_t seed, int32_t groups, int32_t C, int32_t L, rocket_kernels **out);
+size_t rocket_minirocket_fit_workspace_bytes(const rocket_kernels *kernels, int32_t B);
+int rocket_minirocket_fit_bias(rocket_kernels *kernels, const float *x_dev, int32_t B, uint64_t seed,
+                               void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Pruning (section 6: many of the random kernels are of little use to a given problem and can
  * be dropped by the regressor's feature importance).  Creates a new handle that holds kernels
  * index[0..count) of `kernels` (host array; any order, repeats allowed) with their current

@@ -766,6 +766,99 @@ extern "C" int rocket_train_step(rocket_kernels *h, const void *x_dev, int x_is_
     return rocket_sgd_update(h, gw, gb, lr, recentre, hip_stream);
 }
 
+// ------------------------------------------------------------------ MINIROCKET-style variant
+
+extern "C" int rocket_minirocket_kernels(uint64_t seed, int32_t groups, int32_t C, int32_t L, rocket_kernels **out)
+{
+    if (!out) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_kernels: out is NULL");
+    *out = nullptr;
+    if (groups < 1 || C < 1) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_kernels: groups and C must be >= 1");
+    if (groups > INT32_MAX / 84) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_kernels: too many groups");
+    if (L < 9) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_kernels: L must be >= 9");
+    rocket_kernels *h = new (std::nothrow) rocket_kernels;
+    if (!h) return rk_fail(ROCKET_ENOMEM, "rocket_minirocket_kernels: out of host memory");
+    try {
+        h->C = C; h->L = L;
+        rk_sample_minirocket(seed, groups, *h);
+        int rc = rk_finish_handle(*h);
+        if (rc != ROCKET_OK) { delete h; return rc; }
+    } catch (const std::bad_alloc &) {
+        delete h;
+        return rk_fail(ROCKET_ENOMEM, "rocket_minirocket_kernels: out of host memory");
+    }
+    *out = h;
+    return ROCKET_OK;
+}
+
+// workspace of the bias fit: [padded batch][outputs of a chunk of kernels][examples][ranks]
+struct FitLayout {
+    size_t ybuf, example, rank, total;
+    int64_t stride;      // floats per row of outputs
+    int32_t chunk;       // kernels per chunk
+};
+
+static FitLayout fit_layout(const rocket_kernels *h, int32_t B)
+{
+    FitLayout f;
+    f.stride = round_up(static_cast<int64_t>(h->L) + 2LL * h->pad_max, 64);
+    const int64_t budget = (64LL << 20) / f.stride;          // rows in 256 MB of outputs
+    f.chunk = static_cast<int32_t>(std::max<int64_t>(1, std::min<int64_t>(h->K, budget)));
+    f.ybuf = padded_batch_bytes(h, B);
+    f.example = f.ybuf + static_cast<size_t>(round_up(static_cast<int64_t>(f.chunk) * f.stride * 4, 256));
+    f.rank = f.example + static_cast<size_t>(round_up(static_cast<int64_t>(h->K) * 4, 256));
+    f.total = f.rank + static_cast<size_t>(round_up(static_cast<int64_t>(h->K) * 4, 256));
+    return f;
+}
+
+extern "C" size_t rocket_minirocket_fit_workspace_bytes(const rocket_kernels *h, int32_t B)
+{
+    if (!h || B < 1) return 0;
+    return fit_layout(h, B).total;
+}
+
+extern "C" int rocket_minirocket_fit_bias(rocket_kernels *h, const float *x_dev, int32_t B, uint64_t seed, void *ws,
+                                          size_t ws_bytes, void *hip_stream)
+{
+    if (!h || !x_dev) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_fit_bias: NULL argument");
+    if (B < 1) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_fit_bias: B must be >= 1");
+    if (h->row_len > INT32_MAX) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_fit_bias: series too long");
+    const FitLayout f = fit_layout(h, B);
+    if (!ws || ws_bytes < f.total)
+        return rk_fail(ROCKET_EWORKSPACE, "rocket_minirocket_fit_bias: workspace of " + std::to_string(f.total) + " bytes required");
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return rk_fail(ROCKET_EWORKSPACE, "rocket_minirocket_fit_bias: workspace must be 256-byte aligned");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int rc = ensure_device(h, stream);
+    if (rc != ROCKET_OK) return rc;
+    if (h->host_stale && h->update_stream != hip_stream) RK_HIP(hipDeviceSynchronize());   // an earlier in-place update on another stream
+    std::vector<int32_t> example, rank;
+    try {
+        rk_minirocket_draws(seed, *h, B, example, rank);
+    } catch (const std::bad_alloc &) {
+        return rk_fail(ROCKET_ENOMEM, "rocket_minirocket_fit_bias: out of host memory");
+    }
+    char *base = static_cast<char *>(ws);
+    float *xpad = static_cast<float *>(ws);
+    float *ybuf = reinterpret_cast<float *>(base + f.ybuf);
+    int32_t *example_dev = reinterpret_cast<int32_t *>(base + f.example);
+    int32_t *rank_dev = reinterpret_cast<int32_t *>(base + f.rank);
+    // pageable sources: the copies return once the host arrays have been read
+    RK_HIP(hipMemcpyAsync(example_dev, example.data(), example.size() * 4, hipMemcpyHostToDevice, stream));
+    RK_HIP(hipMemcpyAsync(rank_dev, rank.data(), rank.size() * 4, hipMemcpyHostToDevice, stream));
+    RK_HIP(hipStreamSynchronize(stream));
+    if (rk_launch_pad(h, x_dev, B, xpad, stream) != ROCKET_OK)
+        return rk_fail(ROCKET_EHIP, "launch of the padding kernel failed");
+    for (int32_t k0 = 0; k0 < h->K; k0 += f.chunk) {
+        const int32_t count = std::min(f.chunk, h->K - k0);
+        if (rk_launch_minirocket_outputs(h, xpad, example_dev, k0, count, f.stride, ybuf, stream) != ROCKET_OK ||
+            rk_launch_minirocket_select(h, rank_dev, k0, count, f.stride, ybuf, stream) != ROCKET_OK)
+            return rk_fail(ROCKET_EHIP, "launch of the bias fitting kernels failed");
+    }
+    // the device records hold the new biases; the host copy is refreshed on demand (as after rocket_sgd_update)
+    h->host_stale = true;
+    h->update_stream = hip_stream;
+    return ROCKET_OK;
+}
+
 // ------------------------------------------------------------------ pruning
 
 extern "C" int rocket_kernels_subset(const rocket_kernels *h, const int32_t *index, int32_t count, rocket_kernels **out)

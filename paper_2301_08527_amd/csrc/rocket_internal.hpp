@@ -88,6 +88,18 @@ int rk_fail(int code, const std::string &msg);
 
 // sampler.cpp: fills the per-kernel arrays of `h` (K, C, L already set)
 void rk_sample_kernels(uint64_t seed, rocket_kernels &h);
+// sampler.cpp: the MINIROCKET-style kernel set (groups of 84 two-valued kernels; C, L already set) and the
+// (training example, rank) draws of the biases
+void rk_sample_minirocket(uint64_t seed, int32_t groups, rocket_kernels &h);
+void rk_minirocket_draws(uint64_t seed, const rocket_kernels &h, int32_t n_train, std::vector<int32_t> &example,
+                         std::vector<int32_t> &rank);
+// rocket_minirocket.hip: bias-free outputs of kernels [k0, k0 + count) on their drawn examples into ybuf (rows of
+// `stride` floats), and the selection of the drawn order statistic, whose negative becomes the kernel's bias in
+// the device records
+int rk_launch_minirocket_outputs(const rocket_kernels *h, const float *xpad, const int32_t *example_dev, int32_t k0,
+                                 int32_t count, int64_t stride, float *ybuf, void *stream);
+int rk_launch_minirocket_select(const rocket_kernels *h, const int32_t *rank_dev, int32_t k0, int32_t count,
+                                int64_t stride, const float *ybuf, void *stream);
 // rocket_api.hip: offsets, job plan, padded row geometry; returns ROCKET_OK or an error
 int rk_finish_handle(rocket_kernels &h);
 

@@ -138,3 +138,73 @@ void rk_sample_kernels(uint64_t seed, rocket_kernels &h)
         h.padding[k] = same ? ((len - 1) * dil) / 2 : 0;
     }
 }
+
+// ------------------------------------------------------------------ MINIROCKET-style kernels
+//
+// The paper's related-work section describes MINIROCKET as: two-valued ("binary") kernels, so that the
+// convolution can be done by additions; weights from a predetermined set; biases sampled from the input
+// data; PPV as the only pooled feature.  This build's reading of the rest: length 9, weights -1 and 2 with
+// three 2s (zero sum, like the mean-centred weights of section 3.1), the predetermined set being all
+// C(9,3) = 84 such kernels in lexicographic order of the positions of the 2s; kernels come in groups of 84
+// that share dilation, padding and channel subset, drawn per group by the laws of section 3.1 from the
+// stream of (seed, group): channel count, channels, dilation, padding.
+
+void rk_sample_minirocket(uint64_t seed, int32_t groups, rocket_kernels &h)
+{
+    const int32_t C = h.C, L = h.L;
+    constexpr int32_t kLen = 9, kSet = 84;
+    const int32_t K = groups * kSet;
+    h.K = K;
+    h.length.assign(K, kLen); h.dilation.resize(K); h.padding.resize(K);
+    h.n_ch.resize(K); h.bias.assign(K, 0.f);
+    h.channels.clear(); h.weights.clear();
+    const int32_t max_ch = C < 9 ? C : 9;
+    const double ch_span = log_base2(static_cast<double>(max_ch + 1));
+    std::vector<int32_t> pool(C);
+    for (int32_t g = 0; g < groups; ++g) {
+        KernelStream rng(seed, static_cast<uint64_t>(g));
+        int32_t nch = static_cast<int32_t>(std::floor(two_to_the(rng.unit() * ch_span)));
+        if (nch < 1) nch = 1;
+        if (nch > max_ch) nch = max_ch;
+        std::iota(pool.begin(), pool.end(), 0);
+        for (int32_t i = 0; i < nch; ++i) {
+            const int32_t j = i + static_cast<int32_t>(rng.below(static_cast<uint32_t>(C - i)));
+            std::swap(pool[i], pool[j]);
+        }
+        const double span = log_base2(static_cast<double>(L - 1) / static_cast<double>(kLen - 1));
+        int32_t dil = static_cast<int32_t>(std::floor(two_to_the(rng.unit() * span)));
+        const int32_t dil_max = (L - 1) / (kLen - 1);
+        if (dil < 1) dil = 1;
+        if (dil > dil_max) dil = dil_max;
+        const bool same = (rng.word() & 1u) != 0;
+        int32_t k = g * kSet;
+        for (int32_t a = 0; a < kLen; ++a)
+            for (int32_t b = a + 1; b < kLen; ++b)
+                for (int32_t c = b + 1; c < kLen; ++c, ++k) {     // lexicographic triples (a, b, c)
+                    h.dilation[k] = dil;
+                    h.padding[k] = same ? ((kLen - 1) * dil) / 2 : 0;
+                    h.n_ch[k] = nch;
+                    for (int32_t q = 0; q < nch; ++q) {
+                        h.channels.push_back(pool[q]);
+                        for (int32_t j = 0; j < kLen; ++j) h.weights.push_back(j == a || j == b || j == c ? 2.f : -1.f);
+                    }
+                }
+    }
+}
+
+// Bias draws of kernel k, from the stream of (seed + 1, k): a training example, uniform on [0, n_train), and a
+// level q, uniform on [0, 1); the bias will be minus the order statistic of rank floor(q (n_k - 1)) of the
+// kernel's bias-free output on that example.
+void rk_minirocket_draws(uint64_t seed, const rocket_kernels &h, int32_t n_train, std::vector<int32_t> &example,
+                         std::vector<int32_t> &rank)
+{
+    example.resize(h.K);
+    rank.resize(h.K);
+    for (int32_t k = 0; k < h.K; ++k) {
+        KernelStream rng(seed + 1, static_cast<uint64_t>(k));
+        example[k] = static_cast<int32_t>(rng.below(static_cast<uint32_t>(n_train)));
+        const double q = rng.unit();
+        const int64_t n = static_cast<int64_t>(h.L) + 2LL * h.padding[k] - static_cast<int64_t>(h.length[k] - 1) * h.dilation[k];
+        rank[k] = static_cast<int32_t>(std::floor(q * static_cast<double>(n - 1)));
+    }
+}

@@ -26,6 +26,7 @@ EXPORTS = [
     "rocket_ridge_workspace_bytes", "rocket_ridge_fit", "rocket_ridge_predict", "rocket_infer",
     "rocket_mse_grad", "rocket_sgd_update", "rocket_train_workspace_bytes", "rocket_train_step",
     "rocket_kernels_subset",
+    "rocket_minirocket_kernels", "rocket_minirocket_fit_workspace_bytes", "rocket_minirocket_fit_bias",
     "rocket_free_kernels", "rocket_last_error",
 ]
 
@@ -92,6 +93,10 @@ def load_library():
     lib.rocket_train_step.argtypes = [vp, vp, C.c_int, i32, u32, f32, f32, vp, vp, vp, f32, C.c_int, vp, vp,
                                       C.c_size_t, vp]
     lib.rocket_kernels_subset.argtypes = [vp, vp, i32, C.POINTER(vp)]
+    lib.rocket_minirocket_kernels.argtypes = [u64, i32, i32, i32, C.POINTER(vp)]
+    lib.rocket_minirocket_fit_workspace_bytes.argtypes = [vp, i32]
+    lib.rocket_minirocket_fit_workspace_bytes.restype = C.c_size_t
+    lib.rocket_minirocket_fit_bias.argtypes = [vp, vp, i32, u64, vp, C.c_size_t, vp]
     lib.rocket_free_kernels.argtypes = [vp]
     lib.rocket_free_kernels.restype = None
     lib.rocket_last_error.restype = C.c_char_p
@@ -465,6 +470,31 @@ def rocket_kernels_subset(kernels, index):
     _check(load_library().rocket_kernels_subset(kernels.handle, idx.ctypes.data_as(C.c_void_p), len(idx),
                                                 C.byref(out)))
     return Kernels(out.value)
+
+
+def rocket_minirocket_kernels(seed, groups, C_, L):
+    out = C.c_void_p()
+    _check(load_library().rocket_minirocket_kernels(seed, groups, C_, L, C.byref(out)))
+    return Kernels(out.value)
+
+
+def rocket_minirocket_fit_workspace_bytes(kernels, B):
+    return int(load_library().rocket_minirocket_fit_workspace_bytes(kernels.handle, B))
+
+
+def rocket_minirocket_fit_bias(kernels, x, seed, workspace=None, stream=None):
+    """x: float32 CUDA tensor (B, C, L) of training series; sets the kernels' biases from it."""
+    torch = _torch()
+    if not (x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() == 3):
+        raise RocketError(ROCKET_EINVAL, "x must be a contiguous float32 CUDA tensor of shape (B, C, L)")
+    if x.shape[1] != kernels.C or x.shape[2] != kernels.L:
+        raise RocketError(ROCKET_ESHAPE, "x does not match the kernels' (C, L)")
+    B = x.shape[0]
+    if workspace is None:
+        workspace = torch.empty(rocket_minirocket_fit_workspace_bytes(kernels, B), dtype=torch.uint8, device=x.device)
+    _check(load_library().rocket_minirocket_fit_bias(kernels.handle, x.data_ptr(), B, seed, workspace.data_ptr(),
+                                                     workspace.numel() * workspace.element_size(),
+                                                     _stream_ptr(torch, stream)))
 
 
 def rocket_free_kernels(kernels):

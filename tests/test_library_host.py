@@ -156,6 +156,28 @@ def test_argument_validation_without_gpu():
     rocket.load_library().rocket_free_kernels(None)
 
 
+def test_minirocket_kernel_set_without_gpu():
+    """host-only: the predetermined kernel set equals the oracle's, and bad arguments are errors"""
+    kr = oracle.minirocket_kernels(9, 6, 20, 3000)
+    h = rocket.rocket_minirocket_kernels(9, 6, 20, 3000)
+    v = rocket.rocket_kernels_view_get(h)
+    for name in ("length", "dilation", "padding", "n_ch", "channels", "ch_off", "w_off", "weights", "bias"):
+        assert np.array_equal(v[name], kr[name]), name
+    for bad in ((0, 20, 3000), (6, 0, 3000), (6, 20, 8)):
+        with pytest.raises(rocket.RocketError):
+            rocket.rocket_minirocket_kernels(9, *bad)
+    lib = rocket.load_library()
+    dummy = ctypes.c_void_p(256)
+    assert rocket.rocket_minirocket_fit_workspace_bytes(h, 0) == 0
+    need = rocket.rocket_minirocket_fit_workspace_bytes(h, 4)
+    assert need % 256 == 0 and need > 4 * 20 * 3000 * 4
+    E = rocket.ROCKET_EINVAL
+    assert lib.rocket_minirocket_fit_bias(None, dummy, 4, 1, dummy, 1 << 40, None) == E
+    assert lib.rocket_minirocket_fit_bias(h.handle, None, 4, 1, dummy, 1 << 40, None) == E
+    assert lib.rocket_minirocket_fit_bias(h.handle, dummy, 0, 1, dummy, 1 << 40, None) == E
+    assert lib.rocket_minirocket_fit_bias(h.handle, dummy, 4, 1, dummy, 16, None) == rocket.ROCKET_EWORKSPACE
+
+
 def test_subset_keeps_the_chosen_kernels():
     """host-only: rocket_kernels_subset copies the selected kernels, in the given order"""
     h = rocket.rocket_make_kernels(3, 50, 6, 900)
