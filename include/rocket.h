@@ -264,10 +264,12 @@ int rocket_calibrate_units(double *out, int32_t count, void *hip_stream);
  * minimises ||y - X w - b||^2 + alpha ||w||^2 over (w, b), the intercept b unpenalised.
  * features_dev: device, n x p float32 row-major (the transform's output for n series);
  * targets_dev: device, n float32; alpha > 0.  coef_dev (device, p doubles) and
- * intercept_dev (device, 1 double) receive w and b.  All arithmetic is fp64; the fit
- * solves the n x n dual system, so it needs n <= 4096 (the paper has 677 training
- * examples and p = 20,000).  workspace_dev: rocket_ridge_workspace_bytes(n, p) bytes of
- * device memory, 256-byte aligned.  Asynchronous on hip_stream like the other calls.
+ * intercept_dev (device, 1 double) receive w and b.  All arithmetic is fp64 and every sum
+ * has a fixed order: a fit is reproducible bit for bit.  The fit solves the n x n dual
+ * system (the paper has 677 training examples and p = 20,000), stored densely in the
+ * workspace: n <= 32768, ROCKET_EINVAL beyond.  workspace_dev:
+ * rocket_ridge_workspace_bytes(n, p) bytes of device memory (0 for sizes the fit rejects),
+ * 256-byte aligned.  Asynchronous on hip_stream like the other calls.
  */
 size_t rocket_ridge_workspace_bytes(int32_t n, int32_t p);
 int rocket_ridge_fit(const float *features_dev, const float *targets_dev, int32_t n, int32_t p, double alpha,

@@ -31,8 +31,12 @@ def _check(X, y, alpha):
 
 
 @pytest.mark.parametrize("n,p,alpha", [(1, 3, 1.0), (2, 1, 0.5), (33, 31, 0.1), (64, 40, 2.0), (120, 500, 1.0),
-                                       (257, 1000, 10.0), (100, 65, 1e-3)])
+                                       (257, 1000, 10.0), (100, 65, 1e-3), (32, 17, 1.0), (31, 16, 1.0), (65, 2003, 0.5),
+                                       (300, 1003, 1.0), (1500, 300, 1.0), (4500, 64, 3.0)])
 def test_small_systems(n, p, alpha):
+    """sizes around the 32-column panels and 64-row tiles of the factorisation, feature counts that are no
+    multiple of 4 or 16, more examples than features, and more examples than one workgroup's LDS could hold"""
+    print("ridge", n, p, alpha, flush=True)
     rng = np.random.default_rng(n * 1000 + p)
     X = (rng.standard_normal((n, p)) * rng.uniform(0.2, 3.0, p) + rng.uniform(-2, 2, p)).astype(np.float32)
     y = (X[:, : min(p, 4)].sum(axis=1) * 0.25 + 1.0 + 0.05 * rng.standard_normal(n)).astype(np.float32)
@@ -64,7 +68,7 @@ def test_argument_errors():
         with pytest.raises(rocket.RocketError):
             rocket.rocket_ridge_fit(X, y, alpha)
     with pytest.raises(rocket.RocketError):
-        rocket.rocket_ridge_fit(torch.zeros(5000, 2, device="cuda"), torch.zeros(5000, device="cuda"), 1.0)
+        rocket.rocket_ridge_fit(torch.zeros(32769, 2, device="cuda"), torch.zeros(32769, device="cuda"), 1.0)
     with pytest.raises(rocket.RocketError):
         rocket.rocket_ridge_fit(X, y, 1.0, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
 
