@@ -52,6 +52,7 @@ WORKLOADS = {
     "univariate-tiny": 0,
     "long-20x200k": 4,
     "ridge-677x20000": None,          # the regressor at the paper's sizes: one step = one fit + one 64-row predict
+    "minirocket-20x50k": None,        # MINIROCKET-style variant on the same batch: 119 groups x 84 kernels, PPV only
 }
 
 
@@ -256,6 +257,111 @@ def ridge_bench(args, torch, rocket):
     }))
 
 
+MINIROCKET_GROUPS = 119          # 9,996 kernels, the nearest multiple of 84 below the paper's 10,000
+# vector operations per (group, output position) as the method defines them: the sum of the nine taps (8 adds),
+# nine U_j = 9 T_j - sum (multiply-add: 2 flop each), 36 pair sums, 84 third additions, 84 comparisons; plus
+# n_ch - 1 additions for the channel sum of the position's sample
+MINIROCKET_FLOP_PER_POSITION = 8 + 18 + 36 + 84 + 84
+
+
+def minirocket_record(torch, rocket, synth, steps, warmup, lam, cpu_seconds=12.0, extend=True):
+    """The MINIROCKET-style variant on the batch of the main workload: biases fitted on the first 8 series, then a
+    step is one rocket_minirocket_transform of all 64.  Also times rocket_transform's PPV plane on the same handle
+    (the general multiply-add kernel on the same kernels) and the oracle on a sample."""
+    cfg = synth.CONFIGS[2]
+    B, C, L = cfg["B"], cfg["C"], cfg["L"]
+    x_host = synth.make_input(2, B=B)
+    x = torch.from_numpy(x_host).cuda()
+    h = rocket.rocket_minirocket_kernels(synth.seed_k(2), MINIROCKET_GROUPS, C, L)
+    rocket.rocket_minirocket_fit_bias(h, x[:8], synth.seed_k(2) + 1)
+    torch.cuda.synchronize()
+    v = rocket.rocket_kernels_view_get(h)
+    K = len(v["length"])
+    n_out = (L + 2 * v["padding"].astype(np.int64) - 8 * v["dilation"].astype(np.int64))[::84]
+    n_ch = v["n_ch"].astype(np.int64)[::84]
+    flop = float(np.sum(n_out * (MINIROCKET_FLOP_PER_POSITION + n_ch - 1))) * B
+    out = torch.empty((B, K), dtype=torch.float32, device="cuda")
+    ws = torch.empty(rocket.rocket_minirocket_workspace_bytes(h, B), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        rocket.rocket_minirocket_transform(h, x, out=out, workspace=ws, stream=stream)
+
+    for _ in range(warmup):
+        step()
+    elapsed, per_step = time_steps(torch, step, steps)
+    more = int(min(400, np.ceil(2.0 / (elapsed / steps)))) - steps if extend else 0
+    if more > 0:
+        e2, p2 = time_steps(torch, step, more)
+        elapsed, per_step = elapsed + e2, per_step + p2
+    steps = len(per_step)
+    rocket.rocket_profile_enable(h, True)
+    for _ in range(10):
+        step()
+    torch.cuda.synchronize()
+    launches, ms = rocket.rocket_profile_read(h)
+    rocket.rocket_profile_enable(h, False)
+    kernel_ms = ms / launches
+    achieved = flop / (kernel_ms * 1e-3) / 1e12
+    rec = {
+        "workload": "minirocket-20x50k", "B": B, "C": C, "L": L, "K": K, "groups": MINIROCKET_GROUPS, "features": 2,
+        "what": "PPV of 84 predetermined two-valued kernels per group, biases fitted to data (group kernel)",
+        "value": B * steps / elapsed, "unit": "examples/s", "steps": steps, "ms_per_step": 1e3 * elapsed / steps,
+        "ms_per_step_median": statistics.median(per_step), "ms_per_step_min": min(per_step),
+        "roofline": {
+            "bound": "alu", "achieved": achieved, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": achieved / FP32_VECTOR_PEAK_TFLOPS, "traffic": None, "kernel": "rk_mr_forward",
+            "kernel_ms": kernel_ms, "flop_per_launch": flop,
+            "note": "additions and comparisons count one flop and run one per lane and clock: their ceiling is a "
+                    "quarter of the packed-FMA peak (39.3 TFLOP/s)", "plain_op_ceiling": FP32_VECTOR_PEAK_TFLOPS / 4.0,
+            "frac_of_plain_op_ceiling": achieved / (FP32_VECTOR_PEAK_TFLOPS / 4.0),
+        },
+    }
+    # the same features from the general kernel (9 n_ch multiply-adds per output)
+    fma, _ = rocket.rocket_work_per_series(h)
+    ws2 = torch.empty(rocket.rocket_workspace_bytes(h, B, 2, False), dtype=torch.uint8, device="cuda")
+    out2 = torch.empty((B, K), dtype=torch.float32, device="cuda")
+
+    def general():
+        rocket.rocket_transform(h, x, 2, lam, -3.0, out=out2, workspace=ws2, stream=stream)
+
+    general()
+    e3, p3 = time_steps(torch, general, 5)
+    rec["general_kernel"] = {"value": B * 5 / e3, "unit": "examples/s", "ms_per_step": 1e3 * e3 / 5,
+                             "conv_TFLOPs": 2.0 * fma * B / (e3 / 5) / 1e12,
+                             "speedup_of_group_kernel": (e3 / 5) / (elapsed / steps)}
+    if cpu_seconds > 0:
+        import oracle
+        kr = oracle.minirocket_kernels(synth.seed_k(2), MINIROCKET_GROUPS, C, L)
+        kr["bias"] = v["bias"]
+        n_ex = int(max(1, min(B, round(cpu_seconds * 1.4e9 * oracle.num_threads() / fma))))
+        t0 = time.perf_counter()
+        oracle.minirocket_transform(x_host[:n_ex], kr)
+        dt = time.perf_counter() - t0
+        rec["cpu_baseline"] = {"value": n_ex / dt, "unit": "examples/s", "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "%d example(s) x all %d kernels, %.1f s, fp64" % (n_ex, K, dt)}
+    h.free()
+    return rec
+
+
+def minirocket_bench(args, torch, rocket, synth):
+    rec = minirocket_record(torch, rocket, synth, args.steps, args.warmup, args.lam,
+                            0.0 if args.no_cpu_baseline else 12.0, extend=False)
+    line = {
+        "metric": "examples/sec, MINIROCKET-style PPV features (20ch x 50k, 119 groups x 84 kernels)",
+        "value": rec["value"], "unit": "examples/s", "n_gpus": 1, "steps": rec["steps"], "warmup": args.warmup,
+        "ms_per_step": rec["ms_per_step"], "ms_per_step_median": rec["ms_per_step_median"],
+        "ms_per_step_min": rec["ms_per_step_min"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "B": rec["B"], "C": rec["C"], "L": rec["L"], "K": rec["K"],
+                   "groups": rec["groups"], "features": 2},
+        "roofline": rec["roofline"], "general_kernel": rec["general_kernel"],
+    }
+    if "cpu_baseline" in rec:
+        line["cpu_baseline"] = rec["cpu_baseline"]
+    print(json.dumps(line))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -273,6 +379,9 @@ def main():
 
     if args.workload == "ridge-677x20000":
         ridge_bench(args, torch, rocket)
+        return
+    if args.workload == "minirocket-20x50k":
+        minirocket_bench(args, torch, rocket, synth)
         return
     w = Workload(torch, rocket, synth, args.workload, args.lam, args.batch, args.features)
     cfg_id, B, mask, K, C, L = w.cfg_id, w.B, w.mask, w.K, w.C, w.L
@@ -334,6 +443,7 @@ def main():
         line["series_per_s"] = [sub_record(torch, rocket, synth, n, args.lam) for n in ("univariate-standard", "univariate-tiny")]
         line["fwd_bwd"] = sub_record(torch, rocket, synth, "multivariate-20x50k-grad", args.lam)
         line["long"] = sub_record(torch, rocket, synth, "long-20x200k", args.lam)
+        line["minirocket"] = minirocket_record(torch, rocket, synth, 10, 2, args.lam, cpu_seconds=0.0)
 
     if cfg_id == 2 and not w.train and not args.lean:
         # once with the host-to-device copy of the batch inside the timed region (pinned source)

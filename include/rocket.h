@@ -356,12 +356,27 @@ int rocket_train_step(rocket_kernels *kernels, const void *x_dev, int x_is_u8, i
  * rocket_sgd_update).  workspace_dev: rocket_minirocket_fit_workspace_bytes(kernels, B) bytes, 256-byte
  * aligned.  One-time set-up work, not tuned for speed; it synchronises hip_stream once.
  *
- * The features are rocket_transform with feature_mask = ROCKET_F_PPV: one PPV per kernel (Eq. 1-2).
+ * The features are one PPV per kernel (Eq. 1-2): rocket_transform with feature_mask = ROCKET_F_PPV computes
+ * them like those of any other kernels, and
+ *
+ * rocket_minirocket_transform computes the same features with a kernel made for the predetermined set: the
+ * 84 kernels of a group share their channel-summed input and the nine tap values of every position, so that
+ * one kernel's output costs one addition and one comparison ("convolution by additions", section 2).
+ * x_dev: device, B x C x L float32; out_dev: device, B x K float32, out[b * K + k] = PPV of kernel k.  It
+ * evaluates 3 y = U_a + U_b + U_c with U_j = 9 T_j - (T_0 + ... + T_8) in fp32, a different rounding order
+ * from rocket_transform's multiply-adds: the two agree except at outputs within rounding of zero.
+ * workspace_dev: rocket_minirocket_workspace_bytes(kernels, B) bytes, 256-byte aligned.  Only for handles of
+ * rocket_minirocket_kernels whose weights have not been changed since (biases may be: rocket_minirocket_fit_bias,
+ * rocket_kernels_set_params with weights = NULL); ROCKET_EINVAL otherwise, and the workspace size is 0.
+ * Allocates a few KB of device memory at its first call on a handle.  Asynchronous on hip_stream.
  */
 int rocket_minirocket_kernels(uint64_t seed, int32_t groups, int32_t C, int32_t L, rocket_kernels **out);
 size_t rocket_minirocket_fit_workspace_bytes(const rocket_kernels *kernels, int32_t B);
 int rocket_minirocket_fit_bias(rocket_kernels *kernels, const float *x_dev, int32_t B, uint64_t seed,
                                void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+size_t rocket_minirocket_workspace_bytes(const rocket_kernels *kernels, int32_t B);
+int rocket_minirocket_transform(rocket_kernels *kernels, const float *x_dev, int32_t B, float *out_dev,
+                                void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Pruning (section 6: many of the random kernels are of little use to a given problem and can

@@ -17,7 +17,8 @@ DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-pa
 
 
 KERNEL_TUS = ("rocket_forward.hip", "rocket_forward_short.hip", "rocket_backward.hip", "rocket_ridge.hip",
-              "rocket_prologue.hip", "rocket_train.hip", "rocket_calibrate.hip", "rocket_minirocket.hip")   # translation units that hold device code
+              "rocket_prologue.hip", "rocket_train.hip", "rocket_calibrate.hip", "rocket_minirocket.hip",
+              "rocket_minirocket_forward.hip")   # translation units that hold device code
 HOST_TUS = ("rocket_api.hip",)
 
 

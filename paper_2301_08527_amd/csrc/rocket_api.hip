@@ -301,7 +301,10 @@ extern "C" int rocket_kernels_set_params(rocket_kernels *h, const float *weights
         const int rc = download_params(h);
         if (rc != ROCKET_OK) return rc;
     }
-    if (weights) std::copy(weights, weights + h->weights.size(), h->weights.begin());
+    if (weights) {
+        std::copy(weights, weights + h->weights.size(), h->weights.begin());
+        h->mr_groups = 0;          // no longer the predetermined weight set: the group kernel does not apply
+    }
     if (bias) std::copy(bias, bias + h->K, h->bias.begin());
     h->params_dirty = true;
     return ROCKET_OK;
@@ -382,11 +385,14 @@ extern "C" void rocket_free_kernels(rocket_kernels *h)
     drop_events(h);
     if (h->d_blob) {
         int cur = -1;
+        void *jobs = const_cast<RkMrJob *>(h->d_mr_jobs);
         if (hipGetDevice(&cur) == hipSuccess && cur != h->device && hipSetDevice(h->device) == hipSuccess) {
             (void)hipFree(h->d_blob);
+            if (jobs) (void)hipFree(jobs);
             (void)hipSetDevice(cur);
         } else {
             (void)hipFree(h->d_blob);
+            if (jobs) (void)hipFree(jobs);
         }
     }
     delete h;
@@ -706,6 +712,7 @@ extern "C" int rocket_sgd_update(rocket_kernels *h, const float *grad_w_dev, con
         return rk_fail(ROCKET_EHIP, "launch of the update kernel failed");
     h->host_stale = true;
     h->update_stream = hip_stream;
+    h->mr_groups = 0;              // trained weights are no longer the predetermined set
     return ROCKET_OK;
 }
 
@@ -768,6 +775,47 @@ extern "C" int rocket_train_step(rocket_kernels *h, const void *x_dev, int x_is_
 
 // ------------------------------------------------------------------ MINIROCKET-style variant
 
+// Work items of the group kernel: every group's output cut into tiles whose channel-summed input fits the
+// kMrTileFloats floats of LDS (see RkMrJob), group after group.
+static void minirocket_plan(rocket_kernels &h)
+{
+    h.mr_jobs.clear();
+    for (int32_t g = 0; g < h.mr_groups; ++g) {
+        const int32_t k = g * kMrSet;
+        const int64_t d = h.dilation[k], halo = static_cast<int64_t>(kMrLen - 1) * d;
+        const int64_t n = static_cast<int64_t>(h.L) + 2LL * h.padding[k] - halo;
+        RkMrJob j{};
+        j.group = g;
+        if (d <= kMrLinearMaxD) {
+            const int64_t room = (kMrTileFloats - halo) / 64 * 64;
+            const int64_t tiles = (n + room - 1) / room;
+            const int64_t each = round_up((n + tiles - 1) / tiles, 64);
+            for (int64_t t0 = 0; t0 < n; t0 += each) {
+                j.mode = 0; j.first = static_cast<int32_t>(t0);
+                j.count = static_cast<int32_t>(std::min(each, n - t0));
+                j.width = static_cast<int32_t>(round_up(j.count, 64));
+                j.rows = 1; j.col0 = 0;
+                h.mr_jobs.push_back(j);
+            }
+        } else {
+            const int64_t rows_total = (n + d - 1) / d;
+            const int64_t blocks = (d + 255) / 256;
+            const int64_t width = round_up((d + blocks - 1) / blocks, 64);
+            const int64_t rows_max = kMrTileFloats / width - (kMrLen - 1);
+            const int64_t row_tiles = (rows_total + rows_max - 1) / rows_max;
+            const int64_t each = (rows_total + row_tiles - 1) / row_tiles;
+            for (int64_t r0 = 0; r0 < rows_total; r0 += each)
+                for (int64_t c0 = 0; c0 < d; c0 += width) {
+                    if (r0 * d + c0 >= n) continue;   // the output ends before this block begins
+                    j.mode = 1; j.first = static_cast<int32_t>(r0);
+                    j.rows = static_cast<int32_t>(std::min(each, rows_total - r0));
+                    j.col0 = static_cast<int32_t>(c0); j.width = static_cast<int32_t>(width); j.count = 0;
+                    h.mr_jobs.push_back(j);
+                }
+        }
+    }
+}
+
 extern "C" int rocket_minirocket_kernels(uint64_t seed, int32_t groups, int32_t C, int32_t L, rocket_kernels **out)
 {
     if (!out) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_kernels: out is NULL");
@@ -775,6 +823,7 @@ extern "C" int rocket_minirocket_kernels(uint64_t seed, int32_t groups, int32_t 
     if (groups < 1 || C < 1) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_kernels: groups and C must be >= 1");
     if (groups > INT32_MAX / 84) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_kernels: too many groups");
     if (L < 9) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_kernels: L must be >= 9");
+    if (L > (1 << 28)) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_kernels: L must be at most 2^28");
     rocket_kernels *h = new (std::nothrow) rocket_kernels;
     if (!h) return rk_fail(ROCKET_ENOMEM, "rocket_minirocket_kernels: out of host memory");
     try {
@@ -782,6 +831,8 @@ extern "C" int rocket_minirocket_kernels(uint64_t seed, int32_t groups, int32_t 
         rk_sample_minirocket(seed, groups, *h);
         int rc = rk_finish_handle(*h);
         if (rc != ROCKET_OK) { delete h; return rc; }
+        h->mr_groups = groups;
+        minirocket_plan(*h);
     } catch (const std::bad_alloc &) {
         delete h;
         return rk_fail(ROCKET_ENOMEM, "rocket_minirocket_kernels: out of host memory");
@@ -856,6 +907,52 @@ extern "C" int rocket_minirocket_fit_bias(rocket_kernels *h, const float *x_dev,
     // the device records hold the new biases; the host copy is refreshed on demand (as after rocket_sgd_update)
     h->host_stale = true;
     h->update_stream = hip_stream;
+    return ROCKET_OK;
+}
+
+extern "C" size_t rocket_minirocket_workspace_bytes(const rocket_kernels *h, int32_t B)
+{
+    if (!h || B < 1 || h->mr_groups == 0) return 0;
+    return padded_batch_bytes(h, B) + static_cast<size_t>(round_up(static_cast<int64_t>(B) * h->K * 4, 256));
+}
+
+extern "C" int rocket_minirocket_transform(rocket_kernels *h, const float *x_dev, int32_t B, float *out_dev, void *ws,
+                                           size_t ws_bytes, void *hip_stream)
+{
+    if (!h || !x_dev || !out_dev) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_transform: NULL argument");
+    if (B < 1) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_transform: B must be >= 1");
+    if (h->mr_groups == 0)
+        return rk_fail(ROCKET_EINVAL, "rocket_minirocket_transform: the handle does not hold the predetermined kernel set "
+                       "(it was not made by rocket_minirocket_kernels, or its weights were changed); use rocket_transform");
+    if (rk_grid_groups(B, static_cast<int64_t>(h->mr_jobs.size()), 1) > INT32_MAX || static_cast<int64_t>(B) * h->K > INT32_MAX)
+        return rk_fail(ROCKET_EINVAL, "rocket_minirocket_transform: B times the number of work items exceeds the grid limit");
+    const size_t need = rocket_minirocket_workspace_bytes(h, B);
+    if (!ws || ws_bytes < need)
+        return rk_fail(ROCKET_EWORKSPACE, "rocket_minirocket_transform: workspace of " + std::to_string(need) + " bytes required");
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return rk_fail(ROCKET_EWORKSPACE, "rocket_minirocket_transform: workspace must be 256-byte aligned");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int rc = ensure_device(h, stream);
+    if (rc != ROCKET_OK) return rc;
+    if (!h->d_mr_jobs) {
+        void *jobs = nullptr;
+        const size_t bytes = h->mr_jobs.size() * sizeof(RkMrJob);
+        RK_HIP(hipMalloc(&jobs, bytes));
+        h->d_mr_jobs = static_cast<const RkMrJob *>(jobs);
+        RK_HIP(hipMemcpyAsync(jobs, h->mr_jobs.data(), bytes, hipMemcpyHostToDevice, stream));
+        RK_HIP(hipStreamSynchronize(stream));
+    }
+    float *xpad = static_cast<float *>(ws);
+    int32_t *counts = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + padded_batch_bytes(h, B));
+    if (rk_launch_pad(h, x_dev, B, xpad, stream) != ROCKET_OK || rk_launch_minirocket_clear(h, B, counts, stream) != ROCKET_OK)
+        return rk_fail(ROCKET_EHIP, "launch of the padding kernel failed");
+    rc = profile_mark(h, stream, true);
+    if (rc != ROCKET_OK) return rc;
+    if (rk_launch_minirocket_forward(h, xpad, B, counts, stream) != ROCKET_OK)
+        return rk_fail(ROCKET_EHIP, "launch of the group kernel failed");
+    rc = profile_mark(h, stream, false);
+    if (rc != ROCKET_OK) return rc;
+    if (rk_launch_minirocket_features(h, counts, B, out_dev, stream) != ROCKET_OK)
+        return rk_fail(ROCKET_EHIP, "launch of the feature kernel failed");
     return ROCKET_OK;
 }
 

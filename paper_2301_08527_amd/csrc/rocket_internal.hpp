@@ -25,6 +25,19 @@ constexpr int kFewRowsMax = 24;               // ... and largest number of outpu
 #endif
 constexpr int64_t kTilePositions = RK_TILE_POSITIONS;   // smallest time tile of a forward job, in output positions
 
+// MINIROCKET-style kernel set: groups of kMrSet kernels of length kMrLen (rocket.h)
+constexpr int kMrSet = 84;
+constexpr int kMrLen = 9;
+constexpr int kMrTileFloats = 8192;   // channel-summed samples that one workgroup of the group kernel stages in LDS
+constexpr int kMrLinearMaxD = 512;    // up to this dilation a tile is a run of consecutive positions
+
+// One work item of the group kernel (32 bytes).  mode 0: positions [first, first + count) of the group's
+// output, `width` = count rounded up to 64.  mode 1: rows [first, first + rows) x columns [col0, col0 + width)
+// of the output viewed as rows of d positions.
+struct RkMrJob {
+    int32_t group, mode, first, count, col0, width, rows, reserved;
+};
+
 // One packed record per kernel as the device code reads it (32 bytes).
 struct RkKernelRec {
     int32_t len, dil, pad, nout;
@@ -78,6 +91,13 @@ struct rocket_kernels {
     const int32_t *d_channels = nullptr;
     float *d_weights = nullptr;
 
+    // MINIROCKET-style handles (rocket_minirocket_kernels): number of groups while the weights are the
+    // predetermined set (0 otherwise), work items of the group kernel and their device copy (own allocation,
+    // made at the first rocket_minirocket_transform)
+    int32_t mr_groups = 0;
+    std::vector<RkMrJob> mr_jobs;
+    const RkMrJob *d_mr_jobs = nullptr;
+
     // optional event pairs around the dominant kernel of each call
     bool profile = false;
     std::vector<std::pair<void *, void *>> events;
@@ -100,6 +120,11 @@ int rk_launch_minirocket_outputs(const rocket_kernels *h, const float *xpad, con
                                  int32_t count, int64_t stride, float *ybuf, void *stream);
 int rk_launch_minirocket_select(const rocket_kernels *h, const int32_t *rank_dev, int32_t k0, int32_t count,
                                 int64_t stride, const float *ybuf, void *stream);
+// rocket_minirocket_forward.hip: the PPV features of a MINIROCKET-style handle, group by group: clears the
+// B x K counters, adds every work item's positive counts to them, turns them into features
+int rk_launch_minirocket_clear(const rocket_kernels *h, int32_t B, int32_t *counts, void *stream);
+int rk_launch_minirocket_forward(const rocket_kernels *h, const float *xpad, int32_t B, int32_t *counts, void *stream);
+int rk_launch_minirocket_features(const rocket_kernels *h, const int32_t *counts, int32_t B, float *out, void *stream);
 // rocket_api.hip: offsets, job plan, padded row geometry; returns ROCKET_OK or an error
 int rk_finish_handle(rocket_kernels &h);
 

@@ -27,6 +27,7 @@ EXPORTS = [
     "rocket_mse_grad", "rocket_sgd_update", "rocket_train_workspace_bytes", "rocket_train_step",
     "rocket_kernels_subset",
     "rocket_minirocket_kernels", "rocket_minirocket_fit_workspace_bytes", "rocket_minirocket_fit_bias",
+    "rocket_minirocket_workspace_bytes", "rocket_minirocket_transform",
     "rocket_free_kernels", "rocket_last_error",
 ]
 
@@ -97,6 +98,9 @@ def load_library():
     lib.rocket_minirocket_fit_workspace_bytes.argtypes = [vp, i32]
     lib.rocket_minirocket_fit_workspace_bytes.restype = C.c_size_t
     lib.rocket_minirocket_fit_bias.argtypes = [vp, vp, i32, u64, vp, C.c_size_t, vp]
+    lib.rocket_minirocket_workspace_bytes.argtypes = [vp, i32]
+    lib.rocket_minirocket_workspace_bytes.restype = C.c_size_t
+    lib.rocket_minirocket_transform.argtypes = [vp, vp, i32, vp, vp, C.c_size_t, vp]
     lib.rocket_free_kernels.argtypes = [vp]
     lib.rocket_free_kernels.restype = None
     lib.rocket_last_error.restype = C.c_char_p
@@ -495,6 +499,28 @@ def rocket_minirocket_fit_bias(kernels, x, seed, workspace=None, stream=None):
     _check(load_library().rocket_minirocket_fit_bias(kernels.handle, x.data_ptr(), B, seed, workspace.data_ptr(),
                                                      workspace.numel() * workspace.element_size(),
                                                      _stream_ptr(torch, stream)))
+
+
+def rocket_minirocket_workspace_bytes(kernels, B):
+    return int(load_library().rocket_minirocket_workspace_bytes(kernels.handle, B))
+
+
+def rocket_minirocket_transform(kernels, x, out=None, workspace=None, stream=None):
+    """x: float32 CUDA tensor (B, C, L); returns the (B, K) float32 PPV features of a MINIROCKET-style handle."""
+    torch = _torch()
+    if not (x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() == 3):
+        raise RocketError(ROCKET_EINVAL, "x must be a contiguous float32 CUDA tensor of shape (B, C, L)")
+    if x.shape[1] != kernels.C or x.shape[2] != kernels.L:
+        raise RocketError(ROCKET_ESHAPE, "x does not match the kernels' (C, L)")
+    B = x.shape[0]
+    if out is None:
+        out = torch.empty((B, kernels.K), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(256, rocket_minirocket_workspace_bytes(kernels, B)), dtype=torch.uint8, device=x.device)
+    _check(load_library().rocket_minirocket_transform(kernels.handle, x.data_ptr(), B, out.data_ptr(), workspace.data_ptr(),
+                                                      workspace.numel() * workspace.element_size(),
+                                                      _stream_ptr(torch, stream)))
+    return out
 
 
 def rocket_free_kernels(kernels):

@@ -25,6 +25,9 @@ int rk_launch_minirocket_outputs(const rocket_kernels *, const float *, const in
                                  void *) STUB("mr_outputs")
 int rk_launch_minirocket_select(const rocket_kernels *, const int32_t *, int32_t, int32_t, int64_t, const float *, void *)
     STUB("mr_select")
+int rk_launch_minirocket_clear(const rocket_kernels *, int32_t, int32_t *, void *) STUB("mr_clear")
+int rk_launch_minirocket_forward(const rocket_kernels *, const float *, int32_t, int32_t *, void *) STUB("mr_forward")
+int rk_launch_minirocket_features(const rocket_kernels *, const int32_t *, int32_t, float *, void *) STUB("mr_features")
 extern "C" int rocket_ridge_predict(const float *, int32_t, int32_t, const double *, const double *, double *, void *)
     STUB("ridge_predict")
 
@@ -96,7 +99,15 @@ int main()
     rocket_kernels_view v;
     if (rocket_kernels_view_get(m, &v) != ROCKET_OK || v.K != 7 * 84) return 1;
     if (rocket_minirocket_fit_workspace_bytes(m, 2) == 0) return 1;
+    if (rocket_minirocket_workspace_bytes(m, 2) == 0) return 1;
     rocket_free_kernels(m);
+    // the plan of the group kernel at sizes around its tile limits (short series, one position, long series)
+    const int shapes[][3] = {{1, 1, 9}, {3, 2, 10}, {5, 3, 73}, {9, 1, 4105}, {4, 20, 8193}, {2, 9, 200001}};
+    for (const auto &sh : shapes) {
+        if (rocket_minirocket_kernels(11, sh[0], sh[1], sh[2], &m) != ROCKET_OK) return 1;
+        if (rocket_minirocket_workspace_bytes(m, 3) == 0) return 1;
+        rocket_free_kernels(m);
+    }
     if (rocket_minirocket_kernels(3, 0, 20, 50000, &m) != ROCKET_EINVAL) return 1;
     std::puts("host driver: ok");
     return 0;

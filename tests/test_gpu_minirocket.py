@@ -104,3 +104,88 @@ def test_paper_shape_sample():
     kr_lib = dict(kr0)
     kr_lib["bias"] = bias
     check_forward(x[4:], kr_lib, out.cpu().numpy(), 2, sel=sel)
+    print("minirocket paper shape: group kernel", flush=True)
+    fast = rocket.rocket_minirocket_transform(h, _gpu(x[4:]))
+    torch.cuda.synchronize()
+    check_forward(x[4:], kr_lib, fast.cpu().numpy(), 2, sel=sel)
+
+
+# ---------------------------------------------------------------- the group kernel (rocket_minirocket_transform)
+
+def _group_transform_case(seed, groups, B, C, L, fitted):
+    """features of rocket_minirocket_transform against the oracle (integer counts, the usual PPV rule) and
+    against rocket_transform's PPV plane on the same handle (different rounding order: same rule)"""
+    import torch
+    print("minirocket group kernel", seed, groups, B, C, L, fitted, flush=True)
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((B, C, L)).astype(np.float32)
+    if L >= 64:
+        x += np.sin(np.arange(L, dtype=np.float32) * (6.28318 / 37.0))[None, None, :]     # correlated neighbours, as in real series
+    h = rocket.rocket_minirocket_kernels(seed, groups, C, L)
+    kr = oracle.minirocket_kernels(seed, groups, C, L)
+    if fitted:
+        rocket.rocket_minirocket_fit_bias(h, _gpu(x[: max(1, B // 2)]), seed + 9)
+        torch.cuda.synchronize()
+    else:
+        rocket.rocket_kernels_set_params(h, None, rng.uniform(-2.0, 2.0, kr["K"]).astype(np.float32))
+    out = rocket.rocket_minirocket_transform(h, _gpu(x))
+    plain = rocket.rocket_transform(h, _gpu(x), 2)
+    torch.cuda.synchronize()
+    kr = dict(kr)
+    kr["bias"] = rocket.rocket_kernels_view_get(h)["bias"]
+    assert out.shape == (B, kr["K"])
+    ref = check_forward(x, kr, out.cpu().numpy(), 2)
+    n = ref["n_out"][None, :].astype(np.float64)
+    diff = np.abs(np.rint(out.cpu().numpy().astype(np.float64) * n) - np.rint(plain.cpu().numpy().astype(np.float64) * n))
+    assert np.all(diff <= 2 * ref["ambiguous"])
+    return h, x, out
+
+
+@pytest.mark.parametrize("seed,groups,B,C,L,fitted", [
+    (11, 1, 1, 1, 9, False),          # one output position (or nine with padding)
+    (12, 3, 2, 2, 10, False),
+    (13, 6, 3, 3, 73, True),
+    (14, 12, 8, 4, 1000, True),       # eight series: the per-XCD series mapping
+    (15, 10, 5, 20, 4105, False),     # tiles of consecutive positions, dilations up to 512
+    (16, 30, 3, 6, 9000, True),       # dilations above 512: tiles of rows x columns, ragged last row
+    (17, 24, 8, 9, 20011, False),
+])
+def test_group_kernel_matches_oracle(seed, groups, B, C, L, fitted):
+    _group_transform_case(seed, groups, B, C, L, fitted)
+
+
+def test_group_kernel_covers_both_tile_kinds():
+    """the sizes above do reach both kinds of work item (checked on the kernels, not assumed)"""
+    for seed, groups, C, L in [(16, 30, 6, 9000), (17, 24, 9, 20011)]:
+        d = oracle.minirocket_kernels(seed, groups, C, L)["dilation"][::84]
+        assert (d <= 512).any() and (d > 512).any() and (d > 1024).any() == (L > 10000)
+
+
+def test_group_kernel_is_deterministic_and_reusable():
+    import torch
+    h, x, out = _group_transform_case(21, 8, 8, 5, 3000, True)
+    ws = torch.empty(rocket.rocket_minirocket_workspace_bytes(h, 8), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xAB)                      # the call may not rely on what the workspace held
+    again = rocket.rocket_minirocket_transform(h, _gpu(x), workspace=ws)
+    small = rocket.rocket_minirocket_transform(h, _gpu(x[:3]), workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, again) and torch.equal(out[:3], small)
+
+
+def test_group_kernel_argument_errors():
+    import torch
+    x = torch.zeros(2, 3, 100, device="cuda")
+    plain = rocket.rocket_make_kernels(1, 84, 3, 100)
+    with pytest.raises(rocket.RocketError):
+        rocket.rocket_minirocket_transform(plain, x)
+    h = rocket.rocket_minirocket_kernels(1, 2, 3, 100)
+    with pytest.raises(rocket.RocketError):
+        rocket.rocket_minirocket_transform(h, x, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    rocket.rocket_minirocket_transform(h, x)
+    w = rocket.rocket_kernels_view_get(h)["weights"].copy()
+    rocket.rocket_kernels_set_params(h, w, None)          # weights touched: no longer known to be the predetermined set
+    assert rocket.rocket_minirocket_workspace_bytes(h, 2) == 0
+    with pytest.raises(rocket.RocketError):
+        rocket.rocket_minirocket_transform(h, x)
+    rocket.rocket_transform(h, x, 2)                      # the general path still serves it
+    torch.cuda.synchronize()
