@@ -28,8 +28,15 @@ constexpr int64_t kTilePositions = RK_TILE_POSITIONS;   // smallest time tile of
 // MINIROCKET-style kernel set: groups of kMrSet kernels of length kMrLen (rocket.h)
 constexpr int kMrSet = 84;
 constexpr int kMrLen = 9;
-constexpr int kMrTileFloats = 8192;   // channel-summed samples that one workgroup of the group kernel stages in LDS
-constexpr int kMrLinearMaxD = 512;    // up to this dilation a tile is a run of consecutive positions
+#ifndef RK_MR_TILE
+#define RK_MR_TILE 6144
+#endif
+#ifndef RK_MR_LINEAR_MAXD
+#define RK_MR_LINEAR_MAXD 256
+#endif
+constexpr int kMrTileFloats = RK_MR_TILE;          // channel-summed samples that one workgroup of the group kernel stages in LDS
+constexpr int kMrLinearMaxD = RK_MR_LINEAR_MAXD;   // up to this dilation a tile is a run of consecutive positions
+static_assert(kMrTileFloats >= 16 * kMrLinearMaxD && kMrTileFloats >= 9 * 256, "a tile must hold its halo and at least one row of outputs");
 
 // One work item of the group kernel (32 bytes).  mode 0: positions [first, first + count) of the group's
 // output, `width` = count rounded up to 64.  mode 1: rows [first, first + rows) x columns [col0, col0 + width)

@@ -11,13 +11,14 @@
 // comparison 3 y > -3 bias; the generic kernel spends 9 n_ch multiply-adds on the same output.
 //
 // rk_mr_forward: one workgroup (four wavefronts) per (series, tile of positions of one group).  The
-// channel-summed samples that the tile needs are staged in LDS once: for d <= 512 a tile is a run of
+// channel-summed samples that the tile needs are staged in LDS once: for d <= 256 a tile is a run of
 // consecutive positions and LDS holds that run plus 8 d samples; for larger d the positions are viewed as rows
 // of d (position = row d + column) and a tile is a block of rows x columns, LDS holding rows + 8 rows of it.
 // Either way tap j of the position at LDS index q is at q + j * stride (stride = d, or the block's width).
 // The 84 kernels are taken in two passes of 42 over the staged tile so that 42 counters fit the scalar
 // registers (v_cmp + s_bcnt1 + s_add per output) beside 42 thresholds in vector registers.  Counts are
-// integers and added with atomics: the result does not depend on the order.
+// integers and added with atomics: the result does not depend on the order.  The tile holds 6,144 samples
+// (24 KB: six workgroups per CU); 8,192 and 12,288 measured 15 and 40 % slower, 4,096 10 % slower.
 // rk_mr_features: PPV = count / n per (series, kernel).
 #include <hip/hip_runtime.h>
 
@@ -95,6 +96,45 @@ __device__ __forceinline__ void rk_mr_pass(const float *tile, int stride, int wi
     }
 }
 
+// Fills the LDS tile of a work item with the sum of the group's NCH channels (added in the order of the
+// channel list).  Sample index i of a padded row seen through `series` is x[i - pad]; the outputs need
+// i < reach = n + 8 d, and the zeros that follow the samples of a row extend at least that far.
+template <int NCH>
+__device__ __forceinline__ void rk_mr_stage(float *tile, const float *series, const int32_t *__restrict__ chan,
+                                            int row_len, const RkMrJob &job, int d, int reach, int tid)
+{
+    const float *rows[NCH];
+    rk_static_for<0, NCH>([&](auto cc) {
+        constexpr int c = decltype(cc)::value;
+        rows[c] = series + static_cast<size_t>(chan[c]) * row_len;
+    });
+    auto sum_at = [&](unsigned i) {
+        float v[NCH];
+        const unsigned at = i * 4u;     // a 32-bit byte offset beside a scalar row address: no 64-bit vector arithmetic
+        rk_static_for<0, NCH>([&](auto cc) {
+            constexpr int c = decltype(cc)::value;
+            v[c] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(rows[c]) + at);
+        });
+        float s = v[0];
+        rk_static_for<1, NCH>([&](auto cc) { constexpr int c = decltype(cc)::value; s += v[c]; });
+        return s;
+    };
+    if (job.mode == 0) {
+        // positions [first, first + count): LDS index = position - first
+        const int total = job.count + (kMrLen - 1) * d;
+        for (int u = tid; u < total; u += 256) tile[u] = sum_at(static_cast<unsigned>(job.first + u));
+    } else {
+        // output rows [first, first + rows) x columns [col0, col0 + width): LDS index = row * width + column
+        for (int u = 0; u < job.rows + (kMrLen - 1); ++u) {
+            const int base = (job.first + u) * d + job.col0;
+            for (int c0 = tid; c0 < job.width; c0 += 256) {
+                const int i = base + c0;
+                tile[u * job.width + c0] = i < reach ? sum_at(static_cast<unsigned>(i)) : 0.f;
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void rk_mr_forward(const float *__restrict__ xpad, int row_len, int lead, int C,
                                                      const RkKernelRec *__restrict__ recs,
                                                      const int32_t *__restrict__ channels,
@@ -111,41 +151,29 @@ __global__ __launch_bounds__(256) void rk_mr_forward(const float *__restrict__ x
     const int d = rec.dil, n = rec.nout, nch = rec.nch;
     const int tid = static_cast<int>(threadIdx.x);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    // sample index i of a padded row seen through `series` is x[i - pad]; the outputs need i < n + 8 d, and the
-    // zeros after the samples reach at least that far
     const float *series = xpad + static_cast<size_t>(b) * C * row_len + (lead - rec.pad);
     const int32_t *chan = channels + rec.ch_off;
     const int reach = n + (kMrLen - 1) * d;
 
     int stride, width, rows, width_valid, limit0, limit_step;
     if (job.mode == 0) {
-        // positions [first, first + count): LDS index = position - first
-        const int total = job.count + (kMrLen - 1) * d;
-        for (int u = tid; u < total; u += 256) {
-            const int i = job.first + u;
-            float s = series[static_cast<size_t>(chan[0]) * row_len + i];
-            for (int c = 1; c < nch; ++c) s += series[static_cast<size_t>(chan[c]) * row_len + i];
-            tile[u] = s;
-        }
         stride = d; width = job.width; rows = 1; width_valid = job.count; limit0 = job.count; limit_step = 0;
     } else {
-        // output rows [first, first + rows) x columns [col0, col0 + width): LDS index = row * width + column
-        for (int u = 0; u < job.rows + (kMrLen - 1); ++u) {
-            const int base = (job.first + u) * d + job.col0;
-            for (int c0 = tid; c0 < job.width; c0 += 256) {
-                const int i = base + c0;
-                float s = 0.f;
-                if (i < reach) {
-                    s = series[static_cast<size_t>(chan[0]) * row_len + i];
-                    for (int c = 1; c < nch; ++c) s += series[static_cast<size_t>(chan[c]) * row_len + i];
-                }
-                tile[u * job.width + c0] = s;
-            }
-        }
         stride = job.width; width = job.width; rows = job.rows;
         width_valid = min(job.width, d - job.col0);
         limit0 = n - job.first * d - job.col0;     // valid columns of the block's first row if the output ended in it
         limit_step = -d;
+    }
+    switch (nch) {    // the channel count is a template parameter of the staging loops: loads back to back, no branches
+    case 1: rk_mr_stage<1>(tile, series, chan, row_len, job, d, reach, tid); break;
+    case 2: rk_mr_stage<2>(tile, series, chan, row_len, job, d, reach, tid); break;
+    case 3: rk_mr_stage<3>(tile, series, chan, row_len, job, d, reach, tid); break;
+    case 4: rk_mr_stage<4>(tile, series, chan, row_len, job, d, reach, tid); break;
+    case 5: rk_mr_stage<5>(tile, series, chan, row_len, job, d, reach, tid); break;
+    case 6: rk_mr_stage<6>(tile, series, chan, row_len, job, d, reach, tid); break;
+    case 7: rk_mr_stage<7>(tile, series, chan, row_len, job, d, reach, tid); break;
+    case 8: rk_mr_stage<8>(tile, series, chan, row_len, job, d, reach, tid); break;
+    default: rk_mr_stage<9>(tile, series, chan, row_len, job, d, reach, tid); break;
     }
     __syncthreads();
     rk_mr_pass<0>(tile, stride, width, rows, width_valid, limit0, limit_step, grec, wave_counts[0], wave, lane);

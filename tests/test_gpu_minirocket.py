@@ -146,8 +146,8 @@ def _group_transform_case(seed, groups, B, C, L, fitted):
     (12, 3, 2, 2, 10, False),
     (13, 6, 3, 3, 73, True),
     (14, 12, 8, 4, 1000, True),       # eight series: the per-XCD series mapping
-    (15, 10, 5, 20, 4105, False),     # tiles of consecutive positions, dilations up to 512
-    (16, 30, 3, 6, 9000, True),       # dilations above 512: tiles of rows x columns, ragged last row
+    (15, 10, 5, 20, 4105, False),     # dilations on either side of 256: tiles of consecutive positions and tiles of rows x columns
+    (16, 30, 3, 6, 9000, True),       # many groups of either kind, ragged last row
     (17, 24, 8, 9, 20011, False),
 ])
 def test_group_kernel_matches_oracle(seed, groups, B, C, L, fitted):
@@ -158,7 +158,7 @@ def test_group_kernel_covers_both_tile_kinds():
     """the sizes above do reach both kinds of work item (checked on the kernels, not assumed)"""
     for seed, groups, C, L in [(16, 30, 6, 9000), (17, 24, 9, 20011)]:
         d = oracle.minirocket_kernels(seed, groups, C, L)["dilation"][::84]
-        assert (d <= 512).any() and (d > 512).any() and (d > 1024).any() == (L > 10000)
+        assert (d <= 256).any() and (d > 256).any() and (d > 1024).any() == (L > 10000)
 
 
 def test_group_kernel_is_deterministic_and_reusable():
