@@ -8,9 +8,9 @@
 //                   the order-preserving integer image of the floats (four passes of 8 bits, LDS histograms;
 //                   exact: it returns an element of the row, whatever the ties) and writes its negative into
 //                   the kernel's device record.
-// The transform itself is rocket_transform with the PPV plane: the two weight values -1 and 2 are exact in
-// fp32, so the multiply-adds give what additions would; on this hardware an addition costs what a
-// multiply-add costs, so nothing is gained by replacing them.
+// The features themselves come from rocket_transform's PPV plane (the two weight values -1 and 2 are exact in
+// fp32, so its multiply-adds give what additions would) or from the group kernel in
+// rocket_minirocket_forward.hip, which shares the tap sums between the 84 kernels of a group.
 #include <hip/hip_runtime.h>
 
 #include "rocket_internal.hpp"

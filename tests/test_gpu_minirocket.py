@@ -189,3 +189,37 @@ def test_group_kernel_argument_errors():
         rocket.rocket_minirocket_transform(h, x)
     rocket.rocket_transform(h, x, 2)                      # the general path still serves it
     torch.cuda.synchronize()
+
+
+def test_group_kernel_can_be_captured_in_a_graph():
+    """after its first call on a handle the group transform only launches kernels (the counters are cleared by
+    a kernel, not a memset), so a stream capture records it; every replay must give the eager result for the
+    input that is in the captured buffer at that time"""
+    import torch
+    rng = np.random.default_rng(33)
+    B, C, L, groups = 8, 3, 2500, 6
+    h = rocket.rocket_minirocket_kernels(33, groups, C, L)
+    rocket.rocket_kernels_set_params(h, None, rng.uniform(-1.0, 1.0, 84 * groups).astype(np.float32))
+    xs = [rng.standard_normal((B, C, L)).astype(np.float32) for _ in range(3)]
+    x = _gpu(xs[0])
+    out = torch.empty((B, 84 * groups), dtype=torch.float32, device="cuda")
+    ws = torch.empty(rocket.rocket_minirocket_workspace_bytes(h, B), dtype=torch.uint8, device="cuda")
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        rocket.rocket_minirocket_transform(h, x, out=out, workspace=ws)   # first use: uploads parameters and work items
+    s.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    print("capturing", flush=True)
+    with torch.cuda.graph(graph, stream=s):
+        rocket.rocket_minirocket_transform(h, x, out=out, workspace=ws)
+    for i, xi in enumerate(xs):
+        x.copy_(_gpu(xi))
+        out.fill_(-1.0)
+        torch.cuda.synchronize()
+        print("replay", i, flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out.clone()
+        eager = rocket.rocket_minirocket_transform(h, x)
+        torch.cuda.synchronize()
+        assert torch.equal(got, eager)

@@ -95,6 +95,30 @@ def test_bias_is_the_stated_order_statistic():
     assert checked > kr["K"] // 2
 
 
+def test_rank_never_reaches_the_largest_output():
+    """rank = floor(q (n - 1)) with q < 1 is at most n - 2: with two outputs the bias is always minus the
+    smaller one, with one output minus that one; and over many kernels the relative rank is uniform"""
+    rng = np.random.default_rng(9)
+    kr0 = mr.minirocket_kernels(3, 3, 1, 10)
+    kr0["padding"][:] = 0
+    kr0["dilation"][:] = 1                       # n = 10 - 8 = 2
+    x = rng.standard_normal((4, 1, 10)).astype(np.float32)
+    kr, ex, rank = mr.minirocket_fit_bias(x, kr0, seed=2)
+    assert np.all(rank == 0)
+    for k in range(kr["K"]):
+        y = oracle.conv_output(x[ex[k]], kr0, k)
+        assert len(y) == 2 and kr["bias"][k] == np.float32(-y.min())
+    one = mr.minirocket_kernels(3, 1, 1, 9)
+    one["padding"][:] = 0
+    kr1, ex1, rank1 = mr.minirocket_fit_bias(x[:, :, :9], one, seed=2)
+    assert np.all(rank1 == 0)
+    big = mr.minirocket_kernels(5, 6, 2, 400)
+    _, _, rank_big = mr.minirocket_fit_bias(rng.standard_normal((3, 2, 400)).astype(np.float32), big, seed=3)
+    n = 400 + 2 * big["padding"].astype(np.int64) - 8 * big["dilation"].astype(np.int64)
+    rel = rank_big / np.maximum(n - 1, 1)
+    assert np.all(rank_big <= np.maximum(n - 2, 0)) and abs(rel.mean() - 0.5) < 0.07 and rel.min() < 0.05 and rel.max() > 0.95
+
+
 def test_ramp_closed_form():
     """a linear ramp through a zero-sum kernel without padding gives the constant sum_j w_j * j * d * slope:
     every order statistic equals it, the bias is its negative, and the strict PPV of the ramp is 0"""

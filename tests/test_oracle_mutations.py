@@ -66,6 +66,29 @@ PY_MUTATIONS = [
      "g_max = G[:, :K] if mask & 1 else None", "g_max = None"),
     ("soft plane taken from the wrong columns", "train.py", "test_oracle_train.py",
      "g_soft = G[:, (planes - 1) * K:]", "g_soft = G[:, :K]"),
+    ("two-valued weights that do not sum to zero", "minirocket.py", "test_oracle_minirocket.py",
+     "LOW, HIGH = -1.0, 2.0", "LOW, HIGH = -1.0, 3.0"),
+    ("weight set in the wrong order", "minirocket.py", "test_oracle_minirocket.py",
+     "SET = list(itertools.combinations(range(LENGTH), 3))", "SET = list(itertools.combinations(range(LENGTH), 3))[::-1]"),
+    ("pairs instead of triples", "minirocket.py", "test_oracle_minirocket.py",
+     "SET = list(itertools.combinations(range(LENGTH), 3))", "SET = list(itertools.combinations(range(LENGTH), 2)) * 3"),
+    ("additions with the wrong multiple", "minirocket.py", "test_oracle_minirocket.py",
+     "return 3.0 * high - sum(taps)", "return 2.0 * high - sum(taps)"),
+    ("additions without the padding", "minirocket.py", "test_oracle_minirocket.py",
+     "total[p:p + L] = x[ch].sum(axis=0)", "total[:L] = x[ch].sum(axis=0)"),
+    ("additions on the first channel only", "minirocket.py", "test_oracle_minirocket.py",
+     "total[p:p + L] = x[ch].sum(axis=0)", "total[p:p + L] = x[ch[0]]"),
+    ("bias with the wrong sign", "minirocket.py", "test_oracle_minirocket.py",
+     "bias[k] = np.float32(-np.partition(y, rank[k])[rank[k]])", "bias[k] = np.float32(np.partition(y, rank[k])[rank[k]])"),
+    ("rank counted from the top", "minirocket.py", "test_oracle_minirocket.py",
+     "bias[k] = np.float32(-np.partition(y, rank[k])[rank[k]])",
+     "bias[k] = np.float32(-np.partition(y, len(y) - 1 - rank[k])[len(y) - 1 - rank[k]])"),
+    ("rank from q n instead of q (n - 1)", "minirocket.py", "test_oracle_minirocket.py",
+     "rank[k] = int(math.floor(q[k] * (len(y) - 1)))", "rank[k] = min(len(y) - 1, int(math.floor(q[k] * len(y))) + 1)"),
+    ("bias taken from the first example always", "minirocket.py", "test_oracle_minirocket.py",
+     "y = output_by_additions(x_train[ex[k]], kr, k)", "y = output_by_additions(x_train[0], kr, k)"),
+    ("group dilation beyond the series", "minirocket.py", "test_oracle_minirocket.py",
+     "d = max(1, min(d, (L - 1) // (LENGTH - 1)))", "d = max(1, 2 * d)"),
 ]
 
 
