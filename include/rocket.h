@@ -377,6 +377,16 @@ int rocket_minirocket_fit_bias(rocket_kernels *kernels, const float *x_dev, int3
 size_t rocket_minirocket_workspace_bytes(const rocket_kernels *kernels, int32_t B);
 int rocket_minirocket_transform(rocket_kernels *kernels, const float *x_dev, int32_t B, float *out_dev,
                                 void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+/*
+ * The work items of rocket_minirocket_transform, for tests of its plan (host only).  *items points at *count
+ * records of 8 int32 {group, mode, first, count, col0, width, rows, 0}, valid while the handle lives.
+ * mode 0: output positions [first, first + count) of the group; it stages count + 8 d channel-summed samples.
+ * mode 1: rows [first, first + rows) x columns [col0, col0 + width) of the group's output viewed as rows of d
+ * positions (position = row * d + column; columns beyond d and positions beyond the output are skipped); it
+ * stages (rows + 8) * width samples.  No item stages more than 6,144 samples; width is a multiple of 64.
+ * ROCKET_EINVAL if the handle does not hold the predetermined set.
+ */
+int rocket_minirocket_jobs_view_get(const rocket_kernels *kernels, int32_t *count, const int32_t **items);
 
 /*
  * Pruning (section 6: many of the random kernels are of little use to a given problem and can

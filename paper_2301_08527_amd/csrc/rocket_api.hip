@@ -916,6 +916,16 @@ extern "C" size_t rocket_minirocket_workspace_bytes(const rocket_kernels *h, int
     return padded_batch_bytes(h, B) + static_cast<size_t>(round_up(static_cast<int64_t>(B) * h->K * 4, 256));
 }
 
+extern "C" int rocket_minirocket_jobs_view_get(const rocket_kernels *h, int32_t *count, const int32_t **items)
+{
+    if (!h || !count || !items) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_jobs_view_get: NULL argument");
+    if (h->mr_groups == 0) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_jobs_view_get: the handle does not hold the predetermined kernel set");
+    static_assert(sizeof(RkMrJob) == 8 * sizeof(int32_t), "a work item is eight int32");
+    *count = static_cast<int32_t>(h->mr_jobs.size());
+    *items = reinterpret_cast<const int32_t *>(h->mr_jobs.data());
+    return ROCKET_OK;
+}
+
 extern "C" int rocket_minirocket_transform(rocket_kernels *h, const float *x_dev, int32_t B, float *out_dev, void *ws,
                                            size_t ws_bytes, void *hip_stream)
 {

@@ -27,7 +27,7 @@ EXPORTS = [
     "rocket_mse_grad", "rocket_sgd_update", "rocket_train_workspace_bytes", "rocket_train_step",
     "rocket_kernels_subset",
     "rocket_minirocket_kernels", "rocket_minirocket_fit_workspace_bytes", "rocket_minirocket_fit_bias",
-    "rocket_minirocket_workspace_bytes", "rocket_minirocket_transform",
+    "rocket_minirocket_workspace_bytes", "rocket_minirocket_transform", "rocket_minirocket_jobs_view_get",
     "rocket_free_kernels", "rocket_last_error",
 ]
 
@@ -101,6 +101,7 @@ def load_library():
     lib.rocket_minirocket_workspace_bytes.argtypes = [vp, i32]
     lib.rocket_minirocket_workspace_bytes.restype = C.c_size_t
     lib.rocket_minirocket_transform.argtypes = [vp, vp, i32, vp, vp, C.c_size_t, vp]
+    lib.rocket_minirocket_jobs_view_get.argtypes = [vp, C.POINTER(i32), C.POINTER(C.POINTER(i32))]
     lib.rocket_free_kernels.argtypes = [vp]
     lib.rocket_free_kernels.restype = None
     lib.rocket_last_error.restype = C.c_char_p
@@ -503,6 +504,14 @@ def rocket_minirocket_fit_bias(kernels, x, seed, workspace=None, stream=None):
 
 def rocket_minirocket_workspace_bytes(kernels, B):
     return int(load_library().rocket_minirocket_workspace_bytes(kernels.handle, B))
+
+
+def rocket_minirocket_jobs_view_get(kernels):
+    """(count, 8) int32 array (a copy): group, mode, first, count, col0, width, rows, 0 of every work item."""
+    n = C.c_int32()
+    p = C.POINTER(C.c_int32)()
+    _check(load_library().rocket_minirocket_jobs_view_get(kernels.handle, C.byref(n), C.byref(p)))
+    return np.ctypeslib.as_array(p, shape=(n.value, 8)).copy()
 
 
 def rocket_minirocket_transform(kernels, x, out=None, workspace=None, stream=None):

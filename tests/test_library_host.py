@@ -178,6 +178,43 @@ def test_minirocket_kernel_set_without_gpu():
     assert lib.rocket_minirocket_fit_bias(h.handle, dummy, 4, 1, dummy, 16, None) == rocket.ROCKET_EWORKSPACE
 
 
+@pytest.mark.parametrize("groups,C,L", [(1, 1, 9), (4, 2, 10), (9, 3, 73), (20, 4, 4105), (40, 20, 50000), (12, 9, 200001)])
+def test_minirocket_plan_covers_every_position_once(groups, C, L):
+    """host-only: the work items of the group kernel cover every output position of every group exactly once,
+    and none stages more than the 6,144 samples of its LDS tile"""
+    h = rocket.rocket_minirocket_kernels(17, groups, C, L)
+    v = rocket.rocket_kernels_view_get(h)
+    items = rocket.rocket_minirocket_jobs_view_get(h)
+    assert np.all(items[:, 7] == 0) and set(items[:, 1].tolist()) <= {0, 1}
+    kinds = set()
+    for g in range(groups):
+        d, p = int(v["dilation"][84 * g]), int(v["padding"][84 * g])
+        n = L + 2 * p - 8 * d
+        seen = np.zeros(n, np.int32)
+        mine = items[items[:, 0] == g]
+        assert len(mine) >= 1
+        for _, mode, first, count, col0, width, rows, _ in mine.tolist():
+            assert width % 64 == 0 and width >= 64
+            kinds.add(mode)
+            if mode == 0:
+                assert d <= 256 and 1 <= count <= width < count + 64 and count + 8 * d <= 6144 and rows == 1
+                seen[first:first + count] += 1
+            else:
+                assert d > 256 and width <= 256 and rows >= 1 and (rows + 8) * width <= 6144 and col0 < d
+                cols = np.arange(col0, min(col0 + width, d))
+                t = (first + np.arange(rows))[:, None] * d + cols[None, :]
+                t = t[t < n]
+                assert t.size > 0                  # no work item without work
+                np.add.at(seen, t, 1)
+        assert np.all(seen == 1), (g, d, p, int(seen.min()), int(seen.max()))
+    if L >= 50000:
+        assert kinds == {0, 1}
+    plain = rocket.rocket_make_kernels(1, 84, C, max(L, 11))
+    with pytest.raises(rocket.RocketError):
+        rocket.rocket_minirocket_jobs_view_get(plain)
+    assert rocket.rocket_minirocket_workspace_bytes(plain, 2) == 0 and rocket.rocket_minirocket_workspace_bytes(h, 2) > 0
+
+
 def test_subset_keeps_the_chosen_kernels():
     """host-only: rocket_kernels_subset copies the selected kernels, in the given order"""
     h = rocket.rocket_make_kernels(3, 50, 6, 900)
