@@ -268,25 +268,27 @@ __device__ __forceinline__ void rk_bwd_band(const KernelCtx &k, int row0, int nc
     }
 }
 
-// Kernels with a large dilation have few rows (n / d): all of them, the partial last row
-// included, form one strip per lane, so every input value is loaded once per pass instead of
-// once per band of a 8/4/2/1 cascade.  As in the forward pass the row count is a run-time
+// Rows [row0, row0 + rows) of a kernel with a large dilation, and the partial row after them (`tail`
+// outputs, 0 if none): a whole kernel when it has few rows (n / d), otherwise what a job has left
+// after its bands of 32.  They form one strip per lane, so every input value is loaded once per
+// pass instead of once per band of a 16/8/4/2/1 cascade.  As in the forward pass the row count is a run-time
 // uniform: window rows past it, and window rows that lie wholly in the zero padding, are
 // skipped (loads and multiply-adds) with scalar branches.  The conv's last channel is the
 // weight gradient's first, with its inputs still in registers.
 template <int LEN, int RM>
-__device__ __forceinline__ void rk_bwd_few_rows(const KernelCtx &k, int rows, int tail, float coef, bool want_max,
-                                                float *slots, BwdState &st)
+__device__ __forceinline__ void rk_bwd_few_rows(const KernelCtx &k, int row0, int rows, int tail, float coef,
+                                                bool want_max, float *slots, BwdState &st)
 {
     const int nrows = rows + (tail > 0 ? 1 : 0);            // rows with at least one output
     const int prow = k.pad / k.d;                           // padding in rows: 0 or (LEN-1)/2
     const int data_rows = (k.L + k.d - 1) / k.d;            // input rows that hold samples
     const uint32_t dbytes = static_cast<uint32_t>(k.d) * 4u;
-    // bit i: window row i is needed (i < nrows+LEN-1) and holds samples (0 <= i-prow < data_rows)
+    // bit i: window row row0 + i is needed (i < nrows+LEN-1) and holds samples (0 <= row0+i-prow < data_rows)
     uint32_t live = 0;
     for (int i = 0; i < nrows + LEN - 1; ++i) {
-        if (i >= prow && i - prow < data_rows) live |= 1u << i;
+        if (row0 + i >= prow && row0 + i - prow < data_rows) live |= 1u << i;
     }
+    const uint32_t soff0 = static_cast<uint32_t>(row0) * dbytes;
     // single scalar bit tests on an opaque copy, instead of twenty-odd precomputed lane masks
     auto is_live = [&](int i) {
         uint32_t word = live;
@@ -312,7 +314,7 @@ __device__ __forceinline__ void rk_bwd_few_rows(const KernelCtx &k, int rows, in
             float w[LEN];
 #pragma unroll
             for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
-            uint32_t soff = 0;
+            uint32_t soff = soff0;
             rk_static_for<0, RM + LEN - 1>([&](auto ic) {
                 constexpr int i = decltype(ic)::value;
                 if (is_live(i)) xv[i] = rk_load(row, voff, soff);
@@ -332,7 +334,7 @@ __device__ __forceinline__ void rk_bwd_few_rows(const KernelCtx &k, int rows, in
             float q = 0.f;
             if (o < lim) {                                  // uniform
                 const bool own = o < own_rows;
-                if (want_max && own) rk_track_max(acc[o], o * k.d + r, st);
+                if (want_max && own) rk_track_max(acc[o], (row0 + o) * k.d + r, st);
                 q = rk_q(acc[o], own ? coef : 0.f, k.nl, k.ns);
                 st.qsum += q;
             }
@@ -346,7 +348,7 @@ __device__ __forceinline__ void rk_bwd_few_rows(const KernelCtx &k, int rows, in
             if (cc > 0) {
                 const __amdgpu_buffer_rsrc_t row =
                     rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
-                uint32_t soff = 0;
+                uint32_t soff = soff0;
                 rk_static_for<0, RM + LEN - 1>([&](auto ic) {
                     constexpr int i = decltype(ic)::value;
                     if (is_live(i)) xv[i] = rk_load(row, voff, soff);
@@ -464,24 +466,33 @@ __device__ __forceinline__ void rk_backward_body(const KernelCtx &k, int nout, c
     const int d = k.d;
     const int total_rows = nout / d;
     const int tail = nout - total_rows * d;
-    // the job's rows: whole LDS chunks first (small dilations), then bands of 32 rows, then the
-    // binary remainder; the job that owns the partial last row does it last
-    if ((job.flags & 2) && d >= kFewMinD) {       // uniform: the kernel's only job, large dilation
-        const int nrows = total_rows + (tail > 0 ? 1 : 0);
-        if (nrows <= 8) { rk_bwd_few_rows<LEN, 8>(k, total_rows, tail, coef, want_max, slots, st); return; }
-        if (nrows <= kBwdFewRowsMax) { rk_bwd_few_rows<LEN, kBwdFewRowsMax>(k, total_rows, tail, coef, want_max, slots, st); return; }
-    }
+    // the job's rows: whole LDS chunks first (small dilations), then bands of 32 rows, then what is left
     int row0 = job.row0;
     if (d < kLdsMaxD) row0 = rk_bwd_lds_dispatch<LEN, 1>(k, row0, job.row1, coef, want_max, tile, slots, st);
-    const int rows = job.row1 - row0;   // rows left for the register path
+    int rows = job.row1 - row0;   // rows left for the register path
     const int nb32 = rows >> 5;
-    if (nb32) { rk_bwd_segment<LEN, 32>(k, row0, nb32, d, coef, want_max, slots, st); row0 += nb32 << 5; }
+    if (nb32) { rk_bwd_segment<LEN, 32>(k, row0, nb32, d, coef, want_max, slots, st); row0 += nb32 << 5; rows &= 31; }
+    const int own_tail = (job.flags & 1) ? tail : 0;
+    if (d >= kFewMinD) {          // uniform
+        // With at least kFewMinD columns to a row the rows that are left (fewer than 32, and the partial last
+        // row) form one strip per column with a run-time row count: a whole kernel when it has few rows.
+        if (rows + (own_tail > 0 ? 1 : 0) > kBwdFewRowsMax) {
+            rk_bwd_band<LEN, 16, 2>(k, row0, d, coef, want_max, slots, st);
+            row0 += 16; rows -= 16;
+        }
+        const int nrows = rows + (own_tail > 0 ? 1 : 0);
+        if (nrows == 0) return;
+        if (nrows <= 8) { rk_bwd_few_rows<LEN, 8>(k, row0, rows, own_tail, coef, want_max, slots, st); return; }
+        rk_bwd_few_rows<LEN, kBwdFewRowsMax>(k, row0, rows, own_tail, coef, want_max, slots, st);
+        return;
+    }
+    // smaller dilations: the binary remainder; the job that owns the partial last row does it last
     if (rows & 16) { rk_bwd_band<LEN, 16, 2>(k, row0, d, coef, want_max, slots, st); row0 += 16; }
     if (rows & 8) { rk_bwd_band<LEN, 8, 4>(k, row0, d, coef, want_max, slots, st); row0 += 8; }
     if (rows & 4) { rk_bwd_band<LEN, 4, 8>(k, row0, d, coef, want_max, slots, st); row0 += 4; }
     if (rows & 2) { rk_bwd_band<LEN, 2, 8>(k, row0, d, coef, want_max, slots, st); row0 += 2; }
     if (rows & 1) { rk_bwd_band<LEN, 1, 8>(k, row0, d, coef, want_max, slots, st); row0 += 1; }
-    if ((job.flags & 1) && tail) rk_bwd_band<LEN, 1, 8>(k, total_rows, tail, coef, want_max, slots, st);
+    if (own_tail) rk_bwd_band<LEN, 1, 8>(k, total_rows, own_tail, coef, want_max, slots, st);
 }
 
 // grid: one workgroup per (series, job), mapped by rk_block_to_pair; a job is a time tile of one

@@ -86,26 +86,27 @@ __device__ __forceinline__ void rk_pool1(float z, uint32_t mask, float negbias, 
     rk_pool<1>(one, mask, negbias, nl, ns, st);
 }
 
-// Few-rows path for large dilations: when the whole output has at most RM rows of d
-// positions (d >= n/RM), one strip per column covers every row, so each input is
-// loaded exactly once per channel, whatever the row count (the binary band
-// decomposition would cut such a kernel into short strips with little reuse).
+// Few-rows path for large dilations: rows [row0, row0 + rows) and the partial row after them
+// (`tail` outputs, 0 if none), at most RM rows in all -- a whole kernel when its output has few
+// rows of d positions, otherwise what a job has left after its bands of 32.  One strip per
+// column covers every row, so each input is loaded exactly once per channel, whatever the row
+// count (the binary band decomposition would cut them into short strips with little reuse).
 // The row count is a run-time uniform: window rows past it are skipped with scalar
 // branches.  Window rows that lie entirely in the zero padding ("same" padding
 // with a large dilation puts (len-1)/2 such rows on either side) are skipped too,
 // loads and multiply-adds alike.  The partial last row is handled in the same
 // strip and masked per lane in the pooling.
 template <int LEN, int RM, int NT>
-__device__ __forceinline__ void rk_few_rows(const KernelCtx &k, int rows, int tail, PoolState &st)
+__device__ __forceinline__ void rk_few_rows(const KernelCtx &k, int row0, int rows, int tail, PoolState &st)
 {
     const int nrows = rows + (tail > 0 ? 1 : 0);            // rows with at least one output
     const int prow = k.pad / k.d;                           // padding in rows: 0 or (LEN-1)/2
     const int data_rows = (k.L + k.d - 1) / k.d;            // input rows that hold samples
     const uint32_t dbytes = static_cast<uint32_t>(k.d) * 4u;
-    // bit i: window row i is needed (i < nrows+LEN-1) and holds samples (0 <= i-prow < data_rows)
+    // bit i: window row row0 + i is needed (i < nrows+LEN-1) and holds samples (0 <= row0+i-prow < data_rows)
     uint32_t live_lo = 0, live_hi = 0;
     for (int i = 0; i < nrows + LEN - 1; ++i) {
-        if (i >= prow && i - prow < data_rows) {
+        if (row0 + i >= prow && row0 + i - prow < data_rows) {
             if (i < 32) live_lo |= 1u << i;
             else live_hi |= 1u << (i - 32);
         }
@@ -136,7 +137,7 @@ __device__ __forceinline__ void rk_few_rows(const KernelCtx &k, int rows, int ta
             for (int j = 0; j < LEN; ++j) w[j] = k.wts[c * LEN + j];
             // all loads first (so they are in flight together), then the multiply-adds
             float xv[RM + LEN - 1];
-            uint32_t soff = 0;
+            uint32_t soff = static_cast<uint32_t>(row0) * dbytes;
             rk_static_for<0, RM + LEN - 1>([&](auto ic) {
                 constexpr int i = decltype(ic)::value;
                 if (is_live(i)) xv[i] = rk_load(row, voff, soff);
@@ -179,17 +180,10 @@ __device__ __forceinline__ void rk_forward_body(const KernelCtx &k, int nout, co
     const int rows = nout / d;            // full rows of d outputs
     const int tail = nout - rows * d;     // outputs of the partial last row
     // every branch below is uniform per workgroup
-    if ((job.flags & 2) && d >= kFewMinD) {
-        const int nrows = rows + (tail > 0 ? 1 : 0);
-        if (nrows <= 8) { rk_few_rows<LEN, 8, NT>(k, rows, tail, st); return; }
-        if (nrows <= 16) { rk_few_rows<LEN, 16, NT>(k, rows, tail, st); return; }
-        if (nrows <= kFewRowsMax) { rk_few_rows<LEN, 24, NT>(k, rows, tail, st); return; }
-    }
     int row0 = job.row0;
     if (d < kLdsMaxD) row0 = rk_lds_dispatch<LEN, 1, NT>(k, row0, job.row1, tile, st);
-    // Register path for the remaining rows: bands of 32, 16, 8, 4, 2 rows, tallest first.
-    // A band height is used when its strips fill the workgroup (bands x d >= NT); rows
-    // that are left go to the next smaller height, and single rows take the rest.
+    // Register path for the remaining rows: bands of 32 rows first.  A band height is used when its
+    // strips fill the workgroup (bands x d >= NT).
     int left = job.row1 - row0;
     auto bands_of = [&](auto rc, bool force) {
         constexpr int R = decltype(rc)::value;
@@ -206,12 +200,27 @@ __device__ __forceinline__ void rk_forward_body(const KernelCtx &k, int nout, co
 #if RK_RMAX >= 32
     bands_of(std::integral_constant<int, 32>{}, false);
 #endif
+    const int own_tail = (job.flags & 1) ? tail : 0;
+    if (d >= kFewMinD) {
+        // With a row of at least kFewMinD columns the rows that are left (fewer than 32, and the partial last
+        // row) go through one strip per column with a run-time row count instead of a cascade of bands of 16, 8,
+        // 4, 2, 1 rows, each of which would load its own window: a whole kernel when it has few rows.
+        if (left + (own_tail > 0 ? 1 : 0) > kFewRowsMax) bands_of(std::integral_constant<int, 16>{}, true);
+        const int nrows = left + (own_tail > 0 ? 1 : 0);
+        if (nrows == 0) return;
+        if (nrows <= 8) { rk_few_rows<LEN, 8, NT>(k, row0, left, own_tail, st); return; }
+        if (nrows <= 16) { rk_few_rows<LEN, 16, NT>(k, row0, left, own_tail, st); return; }
+        rk_few_rows<LEN, 24, NT>(k, row0, left, own_tail, st);
+        return;
+    }
+    // smaller dilations: bands of 16, 8, 4, 2 rows, tallest first; rows that are left go to the next
+    // smaller height, and single rows take the rest
     bands_of(std::integral_constant<int, 16>{}, false);
     bands_of(std::integral_constant<int, 8>{}, false);
     bands_of(std::integral_constant<int, 4>{}, false);
     bands_of(std::integral_constant<int, 2>{}, false);
     bands_of(std::integral_constant<int, 1>{}, true);
-    if ((job.flags & 1) && tail) rk_segment<LEN, 1, NT>(k, rows, 1, tail, st);
+    if (own_tail) rk_segment<LEN, 1, NT>(k, rows, 1, own_tail, st);
 }
 
 // grid: one workgroup per (series, job), a job being a row range of one kernel; the index
