@@ -250,12 +250,17 @@ int rocket_calibrate_fma(double *tflops, void *hip_stream);
  *   ROCKET_CAL_MFMA_F32_4X4X1    TFLOP/s of the 4x4x1 FP32 matrix instruction (all its multiply-adds counted)
  *   ROCKET_CAL_MFMA_VALU_SERIAL  time of matrix wavefronts and vector-FMA wavefronts run together, divided by
  *                                the sum of their times run alone: 1 = the two pipes do not overlap, 0.5 = fully
- * All rates are whole-device.  Takes some tens of milliseconds; allocates and frees 64 MB of device memory.
+ *   ROCKET_CAL_STRIP_VALU        TFLOP/s (useful multiply-adds) of the conv strip as the forward kernel forms it
+ *                                (32 rows x 64 columns per wavefront, length 9, four channels, max + PPV pooling)
+ *   ROCKET_CAL_STRIP_MFMA        the same strip with the multiply-adds as 4x4x1 matrix instructions in Toeplitz
+ *                                form (bit-identical outputs): whether the matrix cores would speed the conv up
+ * All rates are whole-device.  Takes some tens of milliseconds; allocates and frees 70 MB of device memory and
+ * synchronises the stream.  ROCKET_EHIP if the two forms of the strip disagree in any output.
  */
 enum {
     ROCKET_CAL_LOAD_B32_L1 = 0, ROCKET_CAL_LOAD_B32_L2 = 1, ROCKET_CAL_LOAD_B128_L1 = 2, ROCKET_CAL_LOAD_B128_L2 = 3,
     ROCKET_CAL_LOAD_B128_TO_LDS = 4, ROCKET_CAL_LDS_READ_B32 = 5, ROCKET_CAL_MFMA_F32_4X4X1 = 6,
-    ROCKET_CAL_MFMA_VALU_SERIAL = 7, ROCKET_CAL_COUNT = 8
+    ROCKET_CAL_MFMA_VALU_SERIAL = 7, ROCKET_CAL_STRIP_VALU = 8, ROCKET_CAL_STRIP_MFMA = 9, ROCKET_CAL_COUNT = 10
 };
 int rocket_calibrate_units(double *out, int32_t count, void *hip_stream);
 

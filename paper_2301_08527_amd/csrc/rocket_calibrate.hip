@@ -5,7 +5,10 @@
 // assumes the packed two-per-lane form and is twice that.
 #include <hip/hip_runtime.h>
 
+#include <vector>
+
 #include "rocket_internal.hpp"
+#include "rocket_device.hpp"
 
 namespace {
 
@@ -202,6 +205,104 @@ __global__ __launch_bounds__(256) void rk_cal_matrix(int iters, float a0, float 
     if (s == 12345.678f) *sink = s;
 }
 
+// One forward strip per wavefront and pass, as rk_segment forms it (32 rows x 64 columns, kernel length 9, four
+// channels, rows 1,024 floats apart, max + PPV pooling), in two forms that give bit-identical outputs:
+//   MATRIX = false: 40 loads and 288 plain multiply-adds per channel
+//   MATRIX = true : the same 40 loads, then 96 v_mfma_f32_4x4x1_16b_f32 in Toeplitz form -- a block is 4 output rows
+//                   x 4 neighbouring columns, one step per input row; lane l supplies its own column's sample as B
+//                   and w[delta - l % 4] as A (the banded weight operand, built with quad shifts), and receives
+//                   the four rows of its own column
+// Their rates answer whether the matrix cores would speed the conv up.  The weights arrive by value.
+struct RkCalWeights { float w[4][9]; };
+constexpr int kStripRows = 32, kStripLen = 9, kStripWin = kStripRows + kStripLen - 1, kStripCh = 4;
+constexpr int kStripD = 1024, kStripPasses = 24, kStripGroups = 256 * 8;
+typedef float rk_f4 __attribute__((ext_vector_type(4)));
+
+template <bool MATRIX>
+__global__ __launch_bounds__(256) void rk_cal_strip(const float *x, RkCalWeights wts, float threshold,
+                                                    float *__restrict__ lane_max, int *__restrict__ wave_count)
+{
+    const unsigned lane = threadIdx.x & 63u;
+    const unsigned gw = blockIdx.x * 4u + static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
+    const unsigned row_bytes = 16u << 20;             // one channel: 4,096 rows of 1,024 floats
+    const unsigned dbytes = kStripD * 4u;
+    float vmax = -INFINITY;
+    int cnt = 0;
+    for (int s = 0; s < kStripPasses; ++s) {
+        const unsigned col0 = ((gw * kStripPasses + static_cast<unsigned>(s)) * 64u) % kStripD;
+        const unsigned voff = (col0 + lane) * 4u;
+        float acc[kStripRows];
+#pragma unroll
+        for (int i = 0; i < kStripRows; ++i) acc[i] = 0.f;
+        for (int c = 0; c < kStripCh; ++c) {
+            const __amdgpu_buffer_rsrc_t r = rk_row_buffer(reinterpret_cast<const char *>(x) + static_cast<size_t>(c) * row_bytes, row_bytes);
+            float w[kStripLen];
+#pragma unroll
+            for (int j = 0; j < kStripLen; ++j) w[j] = wts.w[c][j];
+            float xs[kStripWin];
+            uint32_t soff = 0;
+            rk_static_for<0, kStripWin>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                xs[i] = rk_load(r, voff, soff);
+                soff = rk_advance(soff, dbytes);
+            });
+            if constexpr (!MATRIX) {
+                rk_static_for<0, kStripWin>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    rk_taps<kStripLen, kStripRows, i>(w, xs[i], acc);
+                });
+            } else {
+                float wt[kStripLen + 3];
+                const bool first = (lane & 3u) == 0u;
+                float run = 0.f;
+                rk_static_for<0, kStripLen + 3>([&](auto dc) {
+                    constexpr int dl = decltype(dc)::value;
+                    const float shifted = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
+                        0, __builtin_bit_cast(int, run), 0x90 /* quad_perm [0,0,1,2] */, 0xF, 0xF, false));
+                    float fresh = 0.f;
+                    if constexpr (dl < kStripLen) fresh = w[dl];
+                    run = first ? fresh : shifted;
+                    wt[dl] = run;
+                });
+                rk_f4 a4[kStripRows / 4];
+#pragma unroll
+                for (int m = 0; m < kStripRows / 4; ++m) a4[m] = rk_f4{acc[4 * m], acc[4 * m + 1], acc[4 * m + 2], acc[4 * m + 3]};
+                __builtin_amdgcn_sched_barrier(0);    // all loads of the channel are requested before the first matrix instruction
+                rk_static_for<0, kStripWin>([&](auto ic) {
+                    constexpr int u = decltype(ic)::value;
+                    rk_static_for<0, kStripRows / 4>([&](auto mc) {
+                        constexpr int m = decltype(mc)::value;
+                        constexpr int dl = u - 4 * m;
+                        if constexpr (dl >= 0 && dl < kStripLen + 3)
+                            a4[m] = __builtin_amdgcn_mfma_f32_4x4x1f32(wt[dl], xs[u], a4[m], 0, 0, 0);
+                    });
+                });
+#pragma unroll
+                for (int m = 0; m < kStripRows / 4; ++m) {
+                    acc[4 * m] = a4[m][0]; acc[4 * m + 1] = a4[m][1]; acc[4 * m + 2] = a4[m][2]; acc[4 * m + 3] = a4[m][3];
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kStripRows; ++i) {
+            vmax = fmaxf(vmax, acc[i]);
+            cnt += __builtin_popcountll(__ballot(acc[i] > threshold));
+        }
+    }
+    lane_max[blockIdx.x * 256 + threadIdx.x] = vmax;
+    if (lane == 0) wave_count[gw] = cnt;
+}
+
+// pseudo-random samples in [-1, 1) for the strips (the other micro-kernels do not care what they load)
+__global__ __launch_bounds__(256) void rk_cal_fill(float *x, size_t n)
+{
+    for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n; i += static_cast<size_t>(gridDim.x) * 256) {
+        uint32_t h = static_cast<uint32_t>(i) * 2654435761u;
+        h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+        x[i] = static_cast<float>(h >> 8) * (1.0f / 8388608.0f) - 1.0f;
+    }
+}
+
 }  // namespace
 
 extern "C" int rocket_calibrate_units(double *out, int32_t count, void *hip_stream)
@@ -213,7 +314,7 @@ extern "C" int rocket_calibrate_units(double *out, int32_t count, void *hip_stre
     hipEvent_t e0 = nullptr, e1 = nullptr;
     hipError_t err = hipMalloc(&buf, bytes);
     if (err == hipSuccess) err = hipMalloc(&sink, 256);
-    if (err == hipSuccess) err = hipMemsetAsync(buf, 0, bytes, stream);
+    if (err == hipSuccess) hipLaunchKernelGGL(rk_cal_fill, dim3(4096), dim3(256), 0, stream, buf, bytes / 4);
     if (err == hipSuccess) err = hipEventCreate(&e0);
     if (err == hipSuccess) err = hipEventCreate(&e1);
     // runs `launch` twice (the first run warms caches and clocks) and returns the second run's milliseconds
@@ -256,10 +357,32 @@ extern "C" int rocket_calibrate_units(double *out, int32_t count, void *hip_stre
     timed([&] { hipLaunchKernelGGL(rk_cal_matrix, dim3(mgroups), dim3(256), 0, stream, miters, 1.0001f, 0.5f, 1, sink); }, ms);
     // 1 = the two kinds of wavefront take as long together as one after the other (no overlap); 0.5 would be full overlap
     out[ROCKET_CAL_MFMA_VALU_SERIAL] = (ms_matrix_half + ms_vector_half) > 0.0 ? ms / (ms_matrix_half + ms_vector_half) : 0.0;
+    // the conv strip in its two forms (useful multiply-adds counted); the 64 MB buffer is the four channels
+    RkCalWeights cw;
+    for (int c = 0; c < 4; ++c)
+        for (int j = 0; j < 9; ++j) cw.w[c][j] = 0.125f * static_cast<float>((c * 9 + j) % 7 - 3);
+    const double sflop = 2.0 * kStripGroups * 4.0 * kStripPasses * 64.0 * kStripRows * kStripLen * kStripCh;
+    const size_t lanes = static_cast<size_t>(kStripGroups) * 256, waves = static_cast<size_t>(kStripGroups) * 4;
+    float *res = nullptr;                 // per form: the lanes' maxima, then the wavefronts' counts
+    if (err == hipSuccess) err = hipMalloc(&res, 2 * (lanes + waves) * 4);
+    float *max_a = res, *max_b = res + lanes + waves;
+    int *cnt_a = reinterpret_cast<int *>(res + lanes), *cnt_b = reinterpret_cast<int *>(max_b + lanes);
+    timed([&] { hipLaunchKernelGGL((rk_cal_strip<false>), dim3(kStripGroups), dim3(256), 0, stream, buf, cw, 0.1f, max_a, cnt_a); }, ms);
+    out[ROCKET_CAL_STRIP_VALU] = tflops(sflop);
+    timed([&] { hipLaunchKernelGGL((rk_cal_strip<true>), dim3(kStripGroups), dim3(256), 0, stream, buf, cw, 0.1f, max_b, cnt_b); }, ms);
+    out[ROCKET_CAL_STRIP_MFMA] = tflops(sflop);
+    bool same = true;
+    if (err == hipSuccess) {
+        std::vector<uint32_t> host(2 * (lanes + waves));
+        err = hipMemcpy(host.data(), res, host.size() * 4, hipMemcpyDeviceToHost);
+        for (size_t i = 0; i < lanes + waves && err == hipSuccess; ++i) same = same && host[i] == host[lanes + waves + i];
+    }
+    if (res) (void)hipFree(res);
     if (e0) (void)hipEventDestroy(e0);
     if (e1) (void)hipEventDestroy(e1);
     if (buf) (void)hipFree(buf);
     if (sink) (void)hipFree(sink);
     if (err != hipSuccess) return rk_fail(ROCKET_EHIP, std::string("rocket_calibrate_units: ") + hipGetErrorString(err));
+    if (!same) return rk_fail(ROCKET_EHIP, "rocket_calibrate_units: the matrix form of the conv strip does not reproduce the vector form");
     return ROCKET_OK;
 }

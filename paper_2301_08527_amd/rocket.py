@@ -338,7 +338,8 @@ def rocket_calibrate_fma(stream=None):
 
 
 CAL_NAMES = ("load_b32_l1_GBps", "load_b32_l2_GBps", "load_b128_l1_GBps", "load_b128_l2_GBps",
-             "load_b128_to_lds_GBps", "lds_read_b32_GBps", "mfma_f32_4x4x1_TFLOPs", "mfma_valu_serial_ratio")
+             "load_b128_to_lds_GBps", "lds_read_b32_GBps", "mfma_f32_4x4x1_TFLOPs", "mfma_valu_serial_ratio",
+             "conv_strip_valu_TFLOPs", "conv_strip_mfma_toeplitz_TFLOPs")
 
 
 def rocket_calibrate_units(stream=None):

@@ -255,3 +255,14 @@ def test_transform_can_be_captured_in_a_graph():
         torch.cuda.synchronize()
         assert np.array_equal(got, eager.cpu().numpy())
         check_forward(xi, kr, got, mask)
+
+
+def test_unit_calibration_runs_and_its_two_conv_strips_agree():
+    """rocket_calibrate_units measures the units that bound the kernels; its conv strip exists in a vector form
+    and a matrix (4x4x1 Toeplitz) form, and the call fails unless the two give the same outputs bit for bit"""
+    u = rocket.rocket_calibrate_units()
+    assert set(u) == set(rocket.CAL_NAMES)
+    for name, v in u.items():
+        assert np.isfinite(v) and v > 0, name
+    assert 0.4 < u["mfma_valu_serial_ratio"] < 1.2
+    assert u["conv_strip_valu_TFLOPs"] < 157.3 and u["conv_strip_mfma_toeplitz_TFLOPs"] < 157.3

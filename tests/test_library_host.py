@@ -150,7 +150,7 @@ def test_argument_validation_without_gpu():
     assert lib.rocket_transform_noalloc(h.handle, dummy, 100000, 3, 10.0, -3.0, dummy, None) == rocket.ROCKET_EWORKSPACE
     assert lib.rocket_jobs_view_get(h.handle, None, None, None, None, None, None) == E
     assert lib.rocket_calibrate_fma(None, None) == E
-    assert lib.rocket_calibrate_units(None, 8, None) == E
+    assert lib.rocket_calibrate_units(None, 10, None) == E
     assert lib.rocket_calibrate_units((ctypes.c_double * 4)(), 4, None) == E      # too few slots
     h.free()
     rocket.load_library().rocket_free_kernels(None)
