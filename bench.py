@@ -310,7 +310,12 @@ def minirocket_record(torch, rocket, synth, steps, warmup, lam, cpu_seconds=12.0
         "ms_per_step_median": statistics.median(per_step), "ms_per_step_min": min(per_step),
         "roofline": {
             "bound": "alu", "achieved": achieved, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": achieved / FP32_VECTOR_PEAK_TFLOPS, "traffic": None, "kernel": "rk_mr_forward",
+            "frac": achieved / FP32_VECTOR_PEAK_TFLOPS,
+            # 599,750 KiB x 1.968 fetched + 31,602 KiB written per launch (L2 fill: Infinity Cache + DRAM), from
+            # profiles/rk_mr_forward_minirocket-20x50k.md; not measured by this run
+            "traffic": 1240980000 if (B, MINIROCKET_GROUPS) == (64, 119) else None,
+            "traffic_kind": "L2 fill (Infinity Cache + DRAM), from profiles/rk_mr_forward_minirocket-20x50k.md",
+            "kernel": "rk_mr_forward",
             "kernel_ms": kernel_ms, "flop_per_launch": flop,
             "note": "additions and comparisons count one flop and run one per lane and clock: their ceiling is a "
                     "quarter of the packed-FMA peak (39.3 TFLOP/s)", "plain_op_ceiling": FP32_VECTOR_PEAK_TFLOPS / 4.0,
