@@ -108,6 +108,12 @@ def test_paper_shape_sample():
     fast = rocket.rocket_minirocket_transform(h, _gpu(x[4:]))
     torch.cuda.synchronize()
     check_forward(x[4:], kr_lib, fast.cpu().numpy(), 2, sel=sel)
+    # a batch of eight, as the benchmark launches it (one series per XCD); its first three rows are those above
+    x8 = np.concatenate([x[4:], synth.make_input(2, B=12)[7:]])
+    fast8 = rocket.rocket_minirocket_transform(h, _gpu(x8))
+    torch.cuda.synchronize()
+    assert torch.equal(fast8[:3], fast)
+    check_forward(x8, kr_lib, fast8.cpu().numpy(), 2, sel=sel[::4], rows=np.arange(3, 8))
 
 
 # ---------------------------------------------------------------- the group kernel (rocket_minirocket_transform)
