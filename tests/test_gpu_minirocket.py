@@ -155,6 +155,7 @@ def _group_transform_case(seed, groups, B, C, L, fitted):
     (15, 10, 5, 20, 4105, False),     # dilations on either side of 256: tiles of consecutive positions and tiles of rows x columns
     (16, 30, 3, 6, 9000, True),       # many groups of either kind, ragged last row
     (17, 24, 8, 9, 20011, False),
+    (18, 8, 1, 2, 200001, True),      # long series: dilations up to 25,000, a hundred column blocks to a row
 ])
 def test_group_kernel_matches_oracle(seed, groups, B, C, L, fitted):
     _group_transform_case(seed, groups, B, C, L, fitted)
