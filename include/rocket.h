@@ -374,6 +374,8 @@ int rocket_train_step(rocket_kernels *kernels, const void *x_dev, int x_is_u8, i
  * rocket_minirocket_kernels whose weights have not been changed since (biases may be: rocket_minirocket_fit_bias,
  * rocket_kernels_set_params with weights = NULL); ROCKET_EINVAL otherwise, and the workspace size is 0.
  * Allocates a few KB of device memory at its first call on a handle.  Asynchronous on hip_stream.
+ * rocket_minirocket_transform_u8 is the same from raw 8-bit samples (device, B x C x L uint8), every
+ * (series, channel) row z-normalised on the way as in rocket_transform_u8 (sections 4.1, 4.3).
  */
 int rocket_minirocket_kernels(uint64_t seed, int32_t groups, int32_t C, int32_t L, rocket_kernels **out);
 size_t rocket_minirocket_fit_workspace_bytes(const rocket_kernels *kernels, int32_t B);
@@ -382,6 +384,8 @@ int rocket_minirocket_fit_bias(rocket_kernels *kernels, const float *x_dev, int3
 size_t rocket_minirocket_workspace_bytes(const rocket_kernels *kernels, int32_t B);
 int rocket_minirocket_transform(rocket_kernels *kernels, const float *x_dev, int32_t B, float *out_dev,
                                 void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+int rocket_minirocket_transform_u8(rocket_kernels *kernels, const uint8_t *x_u8_dev, int32_t B, float *out_dev,
+                                   void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 /*
  * The work items of rocket_minirocket_transform, for tests of its plan (host only).  *items points at *count
  * records of 8 int32 {group, mode, first, count, col0, width, rows, 0}, valid while the handle lives.

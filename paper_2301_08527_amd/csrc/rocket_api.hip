@@ -910,10 +910,17 @@ extern "C" int rocket_minirocket_fit_bias(rocket_kernels *h, const float *x_dev,
     return ROCKET_OK;
 }
 
+// workspace of the group transform: [padded batch][B x K counters][row statistics of the 8-bit entry point]
+static size_t minirocket_counts_bytes(const rocket_kernels *h, int32_t B)
+{
+    return static_cast<size_t>(round_up(static_cast<int64_t>(B) * h->K * 4, 256));
+}
+
 extern "C" size_t rocket_minirocket_workspace_bytes(const rocket_kernels *h, int32_t B)
 {
     if (!h || B < 1 || h->mr_groups == 0) return 0;
-    return padded_batch_bytes(h, B) + static_cast<size_t>(round_up(static_cast<int64_t>(B) * h->K * 4, 256));
+    return padded_batch_bytes(h, B) + minirocket_counts_bytes(h, B) +
+           static_cast<size_t>(round_up(static_cast<int64_t>(B) * h->C * 16, 256));
 }
 
 extern "C" int rocket_minirocket_jobs_view_get(const rocket_kernels *h, int32_t *count, const int32_t **items)
@@ -926,20 +933,21 @@ extern "C" int rocket_minirocket_jobs_view_get(const rocket_kernels *h, int32_t 
     return ROCKET_OK;
 }
 
-extern "C" int rocket_minirocket_transform(rocket_kernels *h, const float *x_dev, int32_t B, float *out_dev, void *ws,
-                                           size_t ws_bytes, void *hip_stream)
+static int minirocket_transform_impl(const char *fn, rocket_kernels *h, const void *x_dev, bool is_u8, int32_t B,
+                                     float *out_dev, void *ws, size_t ws_bytes, void *hip_stream)
 {
-    if (!h || !x_dev || !out_dev) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_transform: NULL argument");
-    if (B < 1) return rk_fail(ROCKET_EINVAL, "rocket_minirocket_transform: B must be >= 1");
+    const std::string who(fn);
+    if (!h || !x_dev || !out_dev) return rk_fail(ROCKET_EINVAL, who + ": NULL argument");
+    if (B < 1) return rk_fail(ROCKET_EINVAL, who + ": B must be >= 1");
     if (h->mr_groups == 0)
-        return rk_fail(ROCKET_EINVAL, "rocket_minirocket_transform: the handle does not hold the predetermined kernel set "
-                       "(it was not made by rocket_minirocket_kernels, or its weights were changed); use rocket_transform");
+        return rk_fail(ROCKET_EINVAL, who + ": the handle does not hold the predetermined kernel set (it was not made "
+                       "by rocket_minirocket_kernels, or its weights were changed); use rocket_transform");
     if (rk_grid_groups(B, static_cast<int64_t>(h->mr_jobs.size()), 1) > INT32_MAX || static_cast<int64_t>(B) * h->K > INT32_MAX)
-        return rk_fail(ROCKET_EINVAL, "rocket_minirocket_transform: B times the number of work items exceeds the grid limit");
+        return rk_fail(ROCKET_EINVAL, who + ": B times the number of work items exceeds the grid limit");
     const size_t need = rocket_minirocket_workspace_bytes(h, B);
     if (!ws || ws_bytes < need)
-        return rk_fail(ROCKET_EWORKSPACE, "rocket_minirocket_transform: workspace of " + std::to_string(need) + " bytes required");
-    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return rk_fail(ROCKET_EWORKSPACE, "rocket_minirocket_transform: workspace must be 256-byte aligned");
+        return rk_fail(ROCKET_EWORKSPACE, who + ": workspace of " + std::to_string(need) + " bytes required");
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return rk_fail(ROCKET_EWORKSPACE, who + ": workspace must be 256-byte aligned");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     int rc = ensure_device(h, stream);
     if (rc != ROCKET_OK) return rc;
@@ -951,9 +959,13 @@ extern "C" int rocket_minirocket_transform(rocket_kernels *h, const float *x_dev
         RK_HIP(hipMemcpyAsync(jobs, h->mr_jobs.data(), bytes, hipMemcpyHostToDevice, stream));
         RK_HIP(hipStreamSynchronize(stream));
     }
+    char *base = static_cast<char *>(ws);
     float *xpad = static_cast<float *>(ws);
-    int32_t *counts = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + padded_batch_bytes(h, B));
-    if (rk_launch_pad(h, x_dev, B, xpad, stream) != ROCKET_OK || rk_launch_minirocket_clear(h, B, counts, stream) != ROCKET_OK)
+    int32_t *counts = reinterpret_cast<int32_t *>(base + padded_batch_bytes(h, B));
+    void *stats = base + padded_batch_bytes(h, B) + minirocket_counts_bytes(h, B);
+    const int padded = is_u8 ? rk_launch_pad_u8(h, static_cast<const uint8_t *>(x_dev), B, xpad, stats, stream)
+                             : rk_launch_pad(h, static_cast<const float *>(x_dev), B, xpad, stream);
+    if (padded != ROCKET_OK || rk_launch_minirocket_clear(h, B, counts, stream) != ROCKET_OK)
         return rk_fail(ROCKET_EHIP, "launch of the padding kernel failed");
     rc = profile_mark(h, stream, true);
     if (rc != ROCKET_OK) return rc;
@@ -964,6 +976,19 @@ extern "C" int rocket_minirocket_transform(rocket_kernels *h, const float *x_dev
     if (rk_launch_minirocket_features(h, counts, B, out_dev, stream) != ROCKET_OK)
         return rk_fail(ROCKET_EHIP, "launch of the feature kernel failed");
     return ROCKET_OK;
+}
+
+extern "C" int rocket_minirocket_transform(rocket_kernels *h, const float *x_dev, int32_t B, float *out_dev, void *ws,
+                                           size_t ws_bytes, void *hip_stream)
+{
+    return minirocket_transform_impl("rocket_minirocket_transform", h, x_dev, false, B, out_dev, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int rocket_minirocket_transform_u8(rocket_kernels *h, const uint8_t *x_u8_dev, int32_t B, float *out_dev,
+                                              void *ws, size_t ws_bytes, void *hip_stream)
+{
+    return minirocket_transform_impl("rocket_minirocket_transform_u8", h, x_u8_dev, true, B, out_dev, ws, ws_bytes,
+                                     hip_stream);
 }
 
 // ------------------------------------------------------------------ pruning

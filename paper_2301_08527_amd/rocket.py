@@ -27,7 +27,8 @@ EXPORTS = [
     "rocket_mse_grad", "rocket_sgd_update", "rocket_train_workspace_bytes", "rocket_train_step",
     "rocket_kernels_subset",
     "rocket_minirocket_kernels", "rocket_minirocket_fit_workspace_bytes", "rocket_minirocket_fit_bias",
-    "rocket_minirocket_workspace_bytes", "rocket_minirocket_transform", "rocket_minirocket_jobs_view_get",
+    "rocket_minirocket_workspace_bytes", "rocket_minirocket_transform", "rocket_minirocket_transform_u8",
+    "rocket_minirocket_jobs_view_get",
     "rocket_free_kernels", "rocket_last_error",
 ]
 
@@ -101,6 +102,7 @@ def load_library():
     lib.rocket_minirocket_workspace_bytes.argtypes = [vp, i32]
     lib.rocket_minirocket_workspace_bytes.restype = C.c_size_t
     lib.rocket_minirocket_transform.argtypes = [vp, vp, i32, vp, vp, C.c_size_t, vp]
+    lib.rocket_minirocket_transform_u8.argtypes = [vp, vp, i32, vp, vp, C.c_size_t, vp]
     lib.rocket_minirocket_jobs_view_get.argtypes = [vp, C.POINTER(i32), C.POINTER(C.POINTER(i32))]
     lib.rocket_free_kernels.argtypes = [vp]
     lib.rocket_free_kernels.restype = None
@@ -515,11 +517,12 @@ def rocket_minirocket_jobs_view_get(kernels):
     return np.ctypeslib.as_array(p, shape=(n.value, 8)).copy()
 
 
-def rocket_minirocket_transform(kernels, x, out=None, workspace=None, stream=None):
+def rocket_minirocket_transform(kernels, x, out=None, workspace=None, stream=None, _dtype="float32",
+                                _entry="rocket_minirocket_transform"):
     """x: float32 CUDA tensor (B, C, L); returns the (B, K) float32 PPV features of a MINIROCKET-style handle."""
     torch = _torch()
-    if not (x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.dim() == 3):
-        raise RocketError(ROCKET_EINVAL, "x must be a contiguous float32 CUDA tensor of shape (B, C, L)")
+    if not (x.is_cuda and x.dtype == getattr(torch, _dtype) and x.is_contiguous() and x.dim() == 3):
+        raise RocketError(ROCKET_EINVAL, "x must be a contiguous %s CUDA tensor of shape (B, C, L)" % _dtype)
     if x.shape[1] != kernels.C or x.shape[2] != kernels.L:
         raise RocketError(ROCKET_ESHAPE, "x does not match the kernels' (C, L)")
     B = x.shape[0]
@@ -527,10 +530,15 @@ def rocket_minirocket_transform(kernels, x, out=None, workspace=None, stream=Non
         out = torch.empty((B, kernels.K), dtype=torch.float32, device=x.device)
     if workspace is None:
         workspace = torch.empty(max(256, rocket_minirocket_workspace_bytes(kernels, B)), dtype=torch.uint8, device=x.device)
-    _check(load_library().rocket_minirocket_transform(kernels.handle, x.data_ptr(), B, out.data_ptr(), workspace.data_ptr(),
-                                                      workspace.numel() * workspace.element_size(),
-                                                      _stream_ptr(torch, stream)))
+    _check(getattr(load_library(), _entry)(kernels.handle, x.data_ptr(), B, out.data_ptr(), workspace.data_ptr(),
+                                           workspace.numel() * workspace.element_size(), _stream_ptr(torch, stream)))
     return out
+
+
+def rocket_minirocket_transform_u8(kernels, x_u8, out=None, workspace=None, stream=None):
+    """x_u8: uint8 CUDA tensor (B, C, L), contiguous; rows are z-normalised inside the call."""
+    return rocket_minirocket_transform(kernels, x_u8, out, workspace, stream, _dtype="uint8",
+                                       _entry="rocket_minirocket_transform_u8")
 
 
 def rocket_free_kernels(kernels):

@@ -230,3 +230,24 @@ def test_group_kernel_can_be_captured_in_a_graph():
         eager = rocket.rocket_minirocket_transform(h, x)
         torch.cuda.synchronize()
         assert torch.equal(got, eager)
+
+
+def test_group_kernel_from_bytes():
+    """rocket_minirocket_transform_u8: raw 8-bit samples, z-normalised inside the call, against the oracle's
+    z-scores through the oracle's transform; a constant row and a saturated row included"""
+    import torch
+    rng = np.random.default_rng(44)
+    B, C, L, groups = 4, 5, 3001, 10
+    raw = rng.integers(60, 200, size=(B, C, L)).astype(np.uint8)
+    raw[1, 2, :] = 77                      # zero variance: becomes zeros
+    raw[2, 0, :] = np.where(rng.random(L) < 0.5, 0, 255).astype(np.uint8)
+    h = rocket.rocket_minirocket_kernels(44, groups, C, L)
+    kr = oracle.minirocket_kernels(44, groups, C, L)
+    rocket.rocket_kernels_set_params(h, None, rng.uniform(-1.5, 1.5, kr["K"]).astype(np.float32))
+    out = rocket.rocket_minirocket_transform_u8(h, _gpu(raw))
+    torch.cuda.synchronize()
+    kr = dict(kr)
+    kr["bias"] = rocket.rocket_kernels_view_get(h)["bias"]
+    check_forward(oracle.znormalize_u8(raw), kr, out.cpu().numpy(), 2)
+    with pytest.raises(rocket.RocketError):
+        rocket.rocket_minirocket_transform_u8(h, _gpu(raw.astype(np.float32)))
