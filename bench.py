@@ -146,8 +146,8 @@ class Workload:
                                         dtype=torch.uint8, device=dev)
         self.transform = rocket.rocket_transform_u8 if self.from_u8 else rocket.rocket_transform
 
-    def backward(self):
-        self.rocket.rocket_soft_ppv_backward(self.h, self.x, self.mask, self.gout, self.lam, -3.0, True,
+    def backward(self, include_max=True):
+        self.rocket.rocket_soft_ppv_backward(self.h, self.x, self.mask, self.gout, self.lam, -3.0, include_max,
                                              grad_w=self.gw, grad_b=self.gb, workspace=self.ws, stream=self.stream)
 
     def step(self):
@@ -159,13 +159,13 @@ class Workload:
         if self.with_grad:
             self.backward()
 
-    def kernel_time(self, steps):
+    def kernel_time(self, steps, include_max=True):
         """Average duration (ms) of the dominant kernel over `steps` launches, from the HIP events the library
         records on the call's stream around that kernel (the backward kernel for the gradient workloads)."""
         self.rocket.rocket_profile_enable(self.h, True)
         for _ in range(steps):
             if self.with_grad:
-                self.backward()
+                self.backward(include_max)
             else:
                 self.transform(self.h, self.x, self.mask, self.lam, -3.0, out=self.out, workspace=self.ws,
                                stream=self.stream)
@@ -226,6 +226,9 @@ def sub_record(torch, rocket, synth, name, lam, min_steps=10, min_seconds=2.0, m
            "value": w.B * steps / elapsed, "unit": unit, "steps": steps, "ms_per_step": 1e3 * elapsed / steps,
            "ms_per_step_median": statistics.median(per_step), "ms_per_step_min": min(per_step),
            "roofline": w.roofline(kernel_ms)}
+    if w.with_grad:
+        # the same backward kernel without the max plane's sub-gradient (no arg-max bookkeeping)
+        rec["backward_kernel_ms_without_max"] = w.kernel_time(5, include_max=False)
     w.free()
     return rec
 
