@@ -7,7 +7,9 @@
  * (paper section 3, parts (1) and (2)), with the backward pass that the soft
  * pooling allows.  Around it: the input prologue for raw 8-bit samples
  * (sections 4.1, 4.3), the ridge regressor on the features (part (3), section
- * 3.3), inference in one call, and a training step on the kernels (section 6).
+ * 3.3), inference in one call, a training step on the kernels (section 6), and
+ * a MINIROCKET-style variant (sections 2 and 6: predetermined two-valued
+ * kernels, biases from the data, PPV only).
  *
  * Notation.  Kernel k has length len in {7,9,11}, dilation d >= 1, padding
  * p in {0, (len-1)d/2}, a bias, a list of n_ch distinct channels and one weight
