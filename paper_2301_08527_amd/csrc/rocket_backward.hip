@@ -513,7 +513,7 @@ __global__ __launch_bounds__(kThreads) void rk_backward(const float *__restrict_
                                                         int plane_max, float lambda, float nl, float ns,
                                                         float *__restrict__ partial, int stride, int B, int spread)
 {
-    __shared__ float tile[kLdsTileWords];
+    __shared__ __attribute__((aligned(16))) float tile[kLdsTileWords];   // 16-byte pieces are written straight into it
     __shared__ float slots[kBwdMaxTerms * kBwdSlots];
     __shared__ float s_q[kWaves];
     __shared__ float s_max[kWaves];

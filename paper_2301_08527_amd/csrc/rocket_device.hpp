@@ -150,24 +150,27 @@ constexpr int kLdsStage = 4;                                      // staged word
 constexpr int rk_tile_words(int nt) { return ((kLdsRows * nt + 10 * (kLdsMaxD - 1)) / (nt * kLdsStage) + 1) * nt * kLdsStage; }
 constexpr int kLdsTileWords = rk_tile_words(kThreads);
 
-// Copies `nin` floats starting `chunk_bytes` into a row to the LDS tile with coalesced
-// loads (rounded up to whole rounds of NT*kLdsStage words: the tile and the
-// workspace slack are sized for that).  Barriers on both sides: nobody still reads the
-// previous contents, and the new contents are visible to all lanes afterwards.
+// Copies `nin` floats starting `chunk_bytes` into a row to the LDS tile (rounded up to whole rounds of
+// NT*kLdsStage words: the tile and the workspace slack are sized for that).  The data go from memory straight
+// into LDS (buffer_load_dwordx4 ... lds: a wavefront moves 1 KB per instruction, lane l's 16 bytes to the
+// wavefront's LDS base + 16 l), not through the vector registers, whose return path is what bounds the
+// register paths of these kernels; the source only has to be 4-byte aligned.  Barriers on both sides: nobody
+// still reads the previous contents, and the new contents are visible to all lanes afterwards.
 template <int NT>
 __device__ __forceinline__ void rk_stage_tile(__amdgpu_buffer_rsrc_t row, uint32_t chunk_bytes, int nin, float *tile)
 {
+    typedef __attribute__((address_space(3))) void *lds_ptr;
     const int tid = static_cast<int>(threadIdx.x);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     __syncthreads();
     for (int base = 0; base < nin; base += NT * kLdsStage) {
-        float v[kLdsStage];
-#pragma unroll
-        for (int u = 0; u < kLdsStage; ++u)
-            v[u] = rk_load(row, static_cast<uint32_t>(tid + u * NT) * 4u,
-                           chunk_bytes + static_cast<uint32_t>(base) * 4u);
-#pragma unroll
-        for (int u = 0; u < kLdsStage; ++u) tile[base + tid + u * NT] = v[u];
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(row, (lds_ptr)(tile + base + wave * (64 * kLdsStage)), 16,
+                                                 static_cast<int>(static_cast<uint32_t>(tid) * 16u),
+                                                 static_cast<int>(chunk_bytes + static_cast<uint32_t>(base) * 4u), 0, 0);
     }
+    // vmcnt(0): the copies have landed (gfx9 encoding: vmcnt[3:0] and [15:14], expcnt[6:4] = 7 and lgkmcnt[11:8] = 15 not waited for)
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
 }
 

@@ -237,7 +237,7 @@ __global__ __launch_bounds__(NT) void rk_forward(const float *__restrict__ xpad,
                                                        const float *__restrict__ weights, uint32_t mask, float nl,
                                                        float ns, float *__restrict__ partials, int B, int spread)
 {
-    __shared__ float tile[rk_tile_words(NT)];
+    __shared__ __attribute__((aligned(16))) float tile[rk_tile_words(NT)];   // 16-byte pieces are written straight into it
     int b, jid;
     if (!rk_block_to_pair(J, B, spread, b, jid)) return;
     const RkJob job = jobs[jid];
