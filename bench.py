@@ -32,14 +32,14 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X datasheet, packed FP32 on the vector 
 # side of that interface and is not told apart from HBM by any counter of the compute dies.
 # (workload, batch, feature mask) -> figures; other shapes report null.
 MEASURED_TRAFFIC = {
-    # 12,580,800 KiB x 1.968 fetched + 58,900 KiB written; 2.013e8 read requests x 128 B + 1.11e6 write requests x 64 B
+    # 9,547,000 KiB x 1.968 fetched + 56,700 KiB written; 1.527e8 read requests x 128 B + 1.05e6 write requests x 64 B
     ("multivariate-20x50k", 64, 3): {
-        "l2_fill_bytes": 25413000000, "dram_bytes": 25840000000,
-        "source": "profiles/rk_forward_multivariate-20x50k.md", "commit": "7cf7a30"},
-    # 23,616,000 KiB x 1.968 fetched + 153,600 KiB written; 3.779e8 read requests x 128 B + 2.94e6 write requests x 64 B
+        "l2_fill_bytes": 19298000000, "dram_bytes": 19613000000,
+        "source": "profiles/rk_forward_multivariate-20x50k.md", "commit": "e304e0a"},
+    # 16,320,000 KiB x 1.968 fetched + 153,600 KiB written; 2.61e8 read requests x 128 B + 2.94e6 write requests x 64 B
     ("multivariate-20x50k-grad", 60, 5): {
-        "l2_fill_bytes": 47750000000, "dram_bytes": 48560000000,
-        "source": "profiles/rk_backward_multivariate-20x50k-grad.md", "commit": "85d9b89"},
+        "l2_fill_bytes": 33046000000, "dram_bytes": 33596000000,
+        "source": "profiles/rk_backward_multivariate-20x50k-grad.md", "commit": "e304e0a"},
 }
 
 WORKLOADS = {
