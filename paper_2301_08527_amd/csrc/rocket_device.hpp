@@ -64,13 +64,19 @@ __device__ __forceinline__ void rk_static_for(F &&f)
 }
 
 // Input value number I of a strip feeds every output it overlaps: acc[I-j] += w[j]*x_I.
-template <int LEN, int R, int I>
+// With FIRST set (the first channel of a strip) an output's first tap, j = 0, starts its sum with a plain
+// product instead of a multiply-add onto a zero that would have to be written first: one vector instruction
+// less per output, the same value (the sign of a zero sum aside, which no feature can see).
+template <int LEN, int R, int I, bool FIRST = false>
 __device__ __forceinline__ void rk_taps(const float (&w)[LEN], float xv, float (&acc)[R])
 {
     rk_static_for<0, LEN>([&](auto jc) {
         constexpr int j = decltype(jc)::value;
         constexpr int o = I - j;
-        if constexpr (o >= 0 && o < R) acc[o] = fmaf(w[j], xv, acc[o]);
+        if constexpr (o >= 0 && o < R) {
+            if constexpr (FIRST && j == 0) acc[o] = w[0] * xv;
+            else acc[o] = fmaf(w[j], xv, acc[o]);
+        }
     });
 }
 

@@ -19,7 +19,7 @@ __device__ __forceinline__ void rk_segment(const KernelCtx &k, int row0, int nba
             const int r = s - band * ncols;
             const uint32_t voff = static_cast<uint32_t>((row0 + band * R) * k.d + r) * 4u;
             float acc[R];
-            auto channel = [&](int c) {
+            auto channel = [&](int c, auto first) {
                 const __amdgpu_buffer_rsrc_t row =
                     rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
                 float w[LEN];
@@ -28,13 +28,12 @@ __device__ __forceinline__ void rk_segment(const KernelCtx &k, int row0, int nba
                 uint32_t soff = 0;
                 rk_static_for<0, R + LEN - 1>([&](auto ic) {
                     constexpr int i = decltype(ic)::value;
-                    rk_taps<LEN, R, i>(w, rk_load(row, voff, soff), acc);
+                    rk_taps<LEN, R, i, decltype(first)::value>(w, rk_load(row, voff, soff), acc);
                     soff = rk_advance(soff, dbytes);
                 });
             };
-#pragma unroll
-            for (int i = 0; i < R; ++i) acc[i] = 0.f;
-            for (int c = 0; c < k.nch; ++c) channel(c);
+            channel(0, std::true_type{});       // starts the sums: no zeroing of the accumulators
+            for (int c = 1; c < k.nch; ++c) channel(c, std::false_type{});
             rk_pool<R>(acc, k.mask, k.negbias, k.nl, k.ns, st);
         }
     }
@@ -57,7 +56,7 @@ __device__ __forceinline__ int rk_lds_bands(const KernelCtx &k, int first_row, i
         const int nin = (gb * R + LEN - 1) * D;     // input floats of this chunk
         const uint32_t chunk_bytes = static_cast<uint32_t>((first_row + band0 * R) * D) * 4u;
         float acc[R];
-        auto channel = [&](int c) {
+        auto channel = [&](int c, auto first) {
             const __amdgpu_buffer_rsrc_t row =
                 rk_row_buffer(k.xk + static_cast<size_t>(k.chans[c]) * k.row_bytes, k.span_bytes);
             float w[LEN];
@@ -67,13 +66,12 @@ __device__ __forceinline__ int rk_lds_bands(const KernelCtx &k, int first_row, i
             if (active) {
                 rk_static_for<0, R + LEN - 1>([&](auto ic) {
                     constexpr int i = decltype(ic)::value;
-                    rk_taps<LEN, R, i>(w, mine[i * D], acc);
+                    rk_taps<LEN, R, i, decltype(first)::value>(w, mine[i * D], acc);
                 });
             }
         };
-#pragma unroll
-        for (int i = 0; i < R; ++i) acc[i] = 0.f;
-        for (int c = 0; c < k.nch; ++c) channel(c);
+        channel(0, std::true_type{});                  // starts the sums (lanes without a strip neither sum nor pool)
+        for (int c = 1; c < k.nch; ++c) channel(c, std::false_type{});
         if (active) rk_pool<R>(acc, k.mask, k.negbias, k.nl, k.ns, st);
     }
     return first_row + nb * R;
